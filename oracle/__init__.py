@@ -1,0 +1,171 @@
+"""ctypes front end of the CPU oracle (``mc_oracle.c``).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg import
+this package.  It shares no code with the HIP library and never imports it.
+Arguments are numpy arrays in the stored dtype (uint16 bf16 bit patterns or
+float32); results are float64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mc_oracle.c")
+_LIB = os.path.join(_HERE, "libmc_oracle.so")
+
+BF16, F32 = 0, 1
+_DTYPES = {"bf16": BF16, "f32": F32}
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (fp64 arithmetic, no fast-math, OpenMP over rows)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        vp, i32, i64, f64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_double
+        lib.mco_num_threads.restype = ctypes.c_int
+        lib.mco_attn_rows.restype = ctypes.c_int
+        lib.mco_attn_rows.argtypes = [i32, vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32, f64,
+                                      i64, vp, vp, vp, vp, vp, vp]
+        lib.mco_prefill_attn_paged.restype = ctypes.c_int
+        lib.mco_prefill_attn_paged.argtypes = [i32, vp, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, i32,
+                                               f64, vp, vp, vp]
+        for f in (lib.mco_kv_pack_layer, lib.mco_kv_unpack_layer):
+            f.restype = ctypes.c_int
+            f.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, i32]
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().mco_num_threads())
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check_stored(a: np.ndarray, dtype: str) -> np.ndarray:
+    want = np.uint16 if dtype == "bf16" else np.float32
+    assert a.dtype == want, f"{dtype} tensors are passed as {want}, got {a.dtype}"
+    return np.ascontiguousarray(a)
+
+
+def _scale(scale: Optional[float], head_dim: int) -> float:
+    return float(scale) if scale else 1.0 / float(np.sqrt(np.float64(head_dim)))
+
+
+def attn_rows(dtype: str, q, k_pool, v_pool, block_tables, prefix_lens, new_lens, num_q_heads: int,
+              num_kv_heads: int, rows, scale: Optional[float] = None, key_lo=None, key_hi=None):
+    """Rows (request, head, chunk row) of prefix-reused causal attention.
+
+    Returns (out [n, D] f64, lse [n] f64, psum [n] f64).  ``key_lo`` /
+    ``key_hi`` restrict each row's keys to [lo, hi) within its visible range.
+    """
+    lib = _load()
+    q, k_pool, v_pool = (_check_stored(x, dtype) for x in (q, k_pool, v_pool))
+    N, Hkv, S, D = k_pool.shape
+    assert Hkv == num_kv_heads and v_pool.shape == k_pool.shape
+    bt = np.ascontiguousarray(block_tables, dtype=np.int32)
+    pl = np.ascontiguousarray(prefix_lens, dtype=np.int32)
+    nl = np.ascontiguousarray(new_lens, dtype=np.int32)
+    B = pl.shape[0]
+    assert bt.ndim == 2 and bt.shape[0] == B
+    assert q.shape == (int(nl.sum()), num_q_heads, D)
+    used = np.concatenate([bt[r, :(int(pl[r]) + int(nl[r]) + S - 1) // S] for r in range(B)]) if B else bt[:0, 0]
+    assert used.size == 0 or (used.min() >= 0 and used.max() < N), "block table id outside the pool"
+    rows = np.ascontiguousarray(rows, dtype=np.int32).reshape(-1, 3)
+    n = rows.shape[0]
+    out = np.zeros((n, D), dtype=np.float64)
+    lse = np.zeros(n, dtype=np.float64)
+    psum = np.zeros(n, dtype=np.float64)
+    klo = None if key_lo is None else np.ascontiguousarray(key_lo, dtype=np.int64)
+    khi = None if key_hi is None else np.ascontiguousarray(key_hi, dtype=np.int64)
+    rc = lib.mco_attn_rows(_DTYPES[dtype], _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(bt), bt.shape[1],
+                           _ptr(pl), _ptr(nl), B, num_q_heads, num_kv_heads, D, S, _scale(scale, D),
+                           n, _ptr(rows), _ptr(klo), _ptr(khi), _ptr(out), _ptr(lse), _ptr(psum))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return out, lse, psum
+
+
+def prefill_attn_paged(dtype: str, q, k_pool, v_pool, block_tables, prefix_lens, new_lens,
+                       num_q_heads: int, num_kv_heads: int, scale: Optional[float] = None):
+    """All rows: (out [total_new, Hq, D] f64, lse [total_new, Hq] f64, psum like lse)."""
+    nl = np.asarray(new_lens, dtype=np.int32)
+    D = k_pool.shape[3]
+    total = int(nl.sum())
+    rows = np.empty((total * num_q_heads, 3), dtype=np.int32)
+    t = 0
+    for r in range(nl.shape[0]):
+        c = int(nl[r])
+        blk = rows[t:t + c * num_q_heads].reshape(c, num_q_heads, 3)
+        blk[:, :, 0] = r
+        blk[:, :, 1] = np.arange(num_q_heads)[None, :]
+        blk[:, :, 2] = np.arange(c)[:, None]
+        t += c * num_q_heads
+    out, lse, psum = attn_rows(dtype, q, k_pool, v_pool, block_tables, prefix_lens, new_lens,
+                               num_q_heads, num_kv_heads, rows, scale)
+    return (out.reshape(total, num_q_heads, D), lse.reshape(total, num_q_heads),
+            psum.reshape(total, num_q_heads))
+
+
+def case_rows(case, rows, scale=None, key_lo=None, key_hi=None):
+    """``attn_rows`` on a workloads.AttnCase-shaped object (duck-typed; nothing imported)."""
+    return attn_rows(case.dtype, case.q, case.k_pool, case.v_pool, case.block_tables, case.prefix_lens,
+                     case.new_lens, case.num_q_heads, case.num_kv_heads, rows, scale, key_lo, key_hi)
+
+
+def case_full(case, scale=None):
+    return prefill_attn_paged(case.dtype, case.q, case.k_pool, case.v_pool, case.block_tables,
+                              case.prefix_lens, case.new_lens, case.num_q_heads, case.num_kv_heads, scale)
+
+
+def kv_pack_layer(k_pool: np.ndarray, v_pool: np.ndarray, page_ids, threads: int = 1):
+    """Gather pages [N, page_bytes] uint8 -> contiguous (k_out, v_out) [n, page_bytes] in list order."""
+    lib = _load()
+    k_pool = np.ascontiguousarray(k_pool).view(np.uint8).reshape(k_pool.shape[0], -1)
+    v_pool = np.ascontiguousarray(v_pool).view(np.uint8).reshape(v_pool.shape[0], -1)
+    ids = np.ascontiguousarray(page_ids, dtype=np.int32)
+    N, pb = k_pool.shape
+    n = ids.shape[0]
+    k_out = np.zeros((n, pb), dtype=np.uint8)
+    v_out = np.zeros((n, pb), dtype=np.uint8)
+    rc = lib.mco_kv_pack_layer(_ptr(k_pool), _ptr(v_pool), N, pb, _ptr(ids), n, _ptr(k_out), _ptr(v_out), threads)
+    if rc != 0:
+        raise ValueError("page id outside the pool")
+    return k_out, v_out
+
+
+def kv_unpack_layer(k_in: np.ndarray, v_in: np.ndarray, page_ids, k_pool: np.ndarray, v_pool: np.ndarray,
+                    threads: int = 1) -> None:
+    """Scatter contiguous pages into the listed pages of (k_pool, v_pool) [N, page_bytes] uint8, in place."""
+    lib = _load()
+    assert k_pool.dtype == np.uint8 and v_pool.dtype == np.uint8 and k_pool.flags.c_contiguous and v_pool.flags.c_contiguous
+    k_in = np.ascontiguousarray(k_in).view(np.uint8).reshape(k_in.shape[0], -1)
+    v_in = np.ascontiguousarray(v_in).view(np.uint8).reshape(v_in.shape[0], -1)
+    ids = np.ascontiguousarray(page_ids, dtype=np.int32)
+    assert len(np.unique(ids)) == len(ids), "unpack needs unique destination pages"
+    N, pb = k_pool.shape
+    n = ids.shape[0]
+    assert k_in.shape == (n, pb) and v_in.shape == (n, pb)
+    rc = lib.mco_kv_unpack_layer(_ptr(k_in), _ptr(v_in), N, pb, _ptr(ids), n, _ptr(k_pool), _ptr(v_pool), threads)
+    if rc != 0:
+        raise ValueError("page id outside the pool")

@@ -1,0 +1,94 @@
+"""Pins for the CPU oracle's layer-wise pack / unpack (Section 5.2 load/store path): byte-exact."""
+import numpy as np
+import pytest
+
+from paper_2407_00079_amd import workloads as W
+
+
+@pytest.mark.parametrize("threads", [1, 4])
+def test_pack_is_a_gather_in_list_order(oracle, threads):
+    pc = W.make_pack_case(3, layers=2, num_pages=64, num_pages_dst=96, page_bytes=4096, n=24)
+    for l in range(pc.layers):
+        k_out, v_out = oracle.kv_pack_layer(pc.k_pools[l], pc.v_pools[l], pc.src_ids, threads)
+        # fancy indexing is numpy's own gather, not the oracle's loop
+        np.testing.assert_array_equal(k_out, pc.k_pools[l][pc.src_ids])
+        np.testing.assert_array_equal(v_out, pc.v_pools[l][pc.src_ids])
+        assert not np.array_equal(k_out, v_out)
+
+
+def test_pack_allows_duplicate_ids(oracle):
+    pc = W.make_pack_case(4, layers=1, num_pages=8, num_pages_dst=64, page_bytes=256, n=40, unique_src=False)
+    assert len(np.unique(pc.src_ids)) < 40
+    k_out, v_out = oracle.kv_pack_layer(pc.k_pools[0], pc.v_pools[0], pc.src_ids)
+    np.testing.assert_array_equal(k_out, pc.k_pools[0][pc.src_ids])
+    np.testing.assert_array_equal(v_out, pc.v_pools[0][pc.src_ids])
+
+
+def test_unpack_scatters_and_leaves_other_pages(oracle):
+    pc = W.make_pack_case(5, layers=1, num_pages=32, num_pages_dst=48, page_bytes=512, n=20)
+    rng = np.random.default_rng(0)
+    k_dst = rng.integers(0, 256, size=(48, 512), dtype=np.uint8)
+    v_dst = rng.integers(0, 256, size=(48, 512), dtype=np.uint8)
+    k_before, v_before = k_dst.copy(), v_dst.copy()
+    k_in, v_in = oracle.kv_pack_layer(pc.k_pools[0], pc.v_pools[0], pc.src_ids)
+    oracle.kv_unpack_layer(k_in, v_in, pc.dst_ids, k_dst, v_dst)
+    # the round trip: page dst[i] of the new pool == page src[i] of the old one
+    for i in range(20):
+        np.testing.assert_array_equal(k_dst[pc.dst_ids[i]], pc.k_pools[0][pc.src_ids[i]])
+        np.testing.assert_array_equal(v_dst[pc.dst_ids[i]], pc.v_pools[0][pc.src_ids[i]])
+    untouched = np.setdiff1d(np.arange(48), pc.dst_ids)
+    np.testing.assert_array_equal(k_dst[untouched], k_before[untouched])
+    np.testing.assert_array_equal(v_dst[untouched], v_before[untouched])
+
+
+def test_pack_after_unpack_and_unpack_after_pack_are_identities(oracle):
+    pc = W.make_pack_case(6, layers=3, num_pages=40, num_pages_dst=40, page_bytes=4096, n=24)
+    for l in range(pc.layers):
+        k_in, v_in = oracle.kv_pack_layer(pc.k_pools[l], pc.v_pools[l], pc.src_ids)
+        k_dst = np.zeros((40, 4096), np.uint8)
+        v_dst = np.zeros((40, 4096), np.uint8)
+        oracle.kv_unpack_layer(k_in, v_in, pc.dst_ids, k_dst, v_dst)
+        k_back, v_back = oracle.kv_pack_layer(k_dst, v_dst, pc.dst_ids)
+        np.testing.assert_array_equal(k_back, k_in)
+        np.testing.assert_array_equal(v_back, v_in)
+        # unpacking what was just packed from the same pool, to the same pages, changes nothing
+        k_same, v_same = pc.k_pools[l].copy(), pc.v_pools[l].copy()
+        oracle.kv_unpack_layer(k_in, v_in, pc.src_ids, k_same, v_same)
+        np.testing.assert_array_equal(k_same, pc.k_pools[l])
+        np.testing.assert_array_equal(v_same, pc.v_pools[l])
+
+
+def test_config1_pages_round_trip(oracle):
+    """The tiny configuration's 24 KV pages (fp32, 1 KV head, head_dim 64: 4096 B a page), 2 layers."""
+    case = W.make_config_attn(1)
+    ids = case.block_tables[0]
+    assert ids.shape == (24,)
+    pb = 16 * 1 * 64 * 4
+    for layer_pools in ((case.k_pool, case.v_pool), (case.v_pool, case.k_pool)):
+        kp = layer_pools[0].view(np.uint8).reshape(64, pb)
+        vp = layer_pools[1].view(np.uint8).reshape(64, pb)
+        k_out, v_out = oracle.kv_pack_layer(kp, vp, ids)
+        np.testing.assert_array_equal(k_out, kp[ids])
+        dst = np.random.default_rng(1).permutation(64)[:24].astype(np.int32)
+        k2 = np.zeros_like(kp)
+        v2 = np.zeros_like(vp)
+        oracle.kv_unpack_layer(k_out, v_out, dst, k2, v2)
+        np.testing.assert_array_equal(k2[dst], kp[ids])
+        np.testing.assert_array_equal(v2[dst], vp[ids])
+
+
+def test_out_of_range_ids_are_rejected(oracle):
+    pc = W.make_pack_case(7, layers=1, num_pages=8, num_pages_dst=8, page_bytes=64, n=4)
+    bad = pc.src_ids.copy()
+    bad[2] = 8
+    with pytest.raises(ValueError):
+        oracle.kv_pack_layer(pc.k_pools[0], pc.v_pools[0], bad)
+    bad[2] = -1
+    with pytest.raises(ValueError):
+        oracle.kv_pack_layer(pc.k_pools[0], pc.v_pools[0], bad)
+
+
+def test_empty_list(oracle):
+    pc = W.make_pack_case(8, layers=1, num_pages=8, num_pages_dst=8, page_bytes=64, n=0)
+    k_out, v_out = oracle.kv_pack_layer(pc.k_pools[0], pc.v_pools[0], pc.src_ids)
+    assert k_out.shape == (0, 64) and v_out.shape == (0, 64)
