@@ -1,0 +1,137 @@
+/*
+ * mc.h - C ABI of the MI355X (gfx950) KVCache-reuse hot path.
+ *
+ * Three operations behind Mooncake's KVCache reuse, as the paper states the
+ * problem (it gives no kernel design):
+ *
+ *   - a prefill node gets the ids of the reusable prefix blocks and of all
+ *     blocks of the request, and finishes prefill of the uncached tokens
+ *     "using the prefix cache", in chunks no longer than prefill_chunk
+ *     (Section 3, steps 1 and 2; Section 5.1);
+ *   - per layer, KVCache is loaded before that layer's attention and stored
+ *     after it, asynchronously, overlapped with compute (Section 5.2;
+ *     Section 3, step 3).
+ *
+ * Conventions for every entry point:
+ *   - "dev" pointers are device memory of the current HIP device, "host"
+ *     pointers are ordinary host memory.  The caller owns every buffer; the
+ *     library never allocates or frees device memory and never synchronises.
+ *   - All device work is enqueued on `hip_stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream) and the call returns at once.
+ *     Host arrays are read before the call returns and may be freed then.
+ *   - Arguments are validated on the host first.  On any status other than
+ *     MC_OK nothing has been launched and no output has been touched.
+ *   - Page ids that live in device memory cannot be range-checked without a
+ *     sync: an id outside [0, num_pages) is undefined behaviour.
+ *   - No exceptions cross this boundary.
+ */
+#ifndef MC_H_
+#define MC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MC_OK = 0,
+  MC_ERR_NULL = 1,        /* a required pointer is NULL */
+  MC_ERR_SHAPE = 2,       /* negative size, Hq % Hkv != 0, block table too short for P + C */
+  MC_ERR_UNSUPPORTED = 3, /* head_dim / page_size / dtype combination with no kernel */
+  MC_ERR_ALIGN = 4,       /* pointer not 16-byte aligned, or page_bytes % 16 != 0 */
+  MC_ERR_RANGE = 5,       /* a size exceeds what the kernels index with 32 bits */
+  MC_ERR_WORKSPACE = 6,   /* workspace NULL or smaller than mc_prefill_attn_workspace_bytes */
+  MC_ERR_HIP = 7          /* the HIP runtime refused a copy or a launch */
+} mc_status;
+
+typedef enum { MC_DTYPE_BF16 = 0, MC_DTYPE_F32 = 1 } mc_dtype;
+
+typedef struct {
+  int32_t num_q_heads;  /* Hq */
+  int32_t num_kv_heads; /* Hkv, divides Hq; query head h reads KV head h / (Hq / Hkv) */
+  int32_t head_dim;     /* D: 128 for bf16, 64 for f32 (one row = 256 bytes) */
+  int32_t page_size;    /* S tokens per page: 16 */
+  int64_t num_pages;    /* N pages in each pool */
+  int32_t dtype;        /* mc_dtype of Q, K, V and O */
+  float softmax_scale;  /* 0 selects 1 / sqrt(head_dim) */
+} mc_attn_params;
+
+/* Human-readable name of a status code (static storage). */
+const char* mc_status_string(mc_status s);
+
+/*
+ * Bytes of device workspace mc_prefill_attn_paged needs for a batch of
+ * `batch` requests with `total_new_tokens` new tokens in all (the per-tile
+ * work list the kernel walks).  Returns 0 for invalid arguments.
+ */
+size_t mc_prefill_attn_workspace_bytes(const mc_attn_params* p, int32_t batch,
+                                       int64_t total_new_tokens);
+
+/*
+ * Prefix-reused, paged, chunked-prefill attention (Section 3 steps 1-2).
+ *
+ * Request r has P_r = prefix_lens[r] tokens whose K/V pages were reused and
+ * C_r = new_lens[r] new tokens; the K/V of the new tokens are already in
+ * their pages.  Row i of the request's chunk is absolute position P_r + i
+ * and attends to keys 0 .. P_r + i (itself included); all prefix keys are
+ * visible to every row.  Key j of request r is
+ * pool[block_tables[r][j / S]][h / (Hq/Hkv)][j % S][:].
+ *
+ *   out[i,h,:] = sum_j softmax_j(scale * q[i,h,:] . K(j)) * V(j)
+ *   lse[i,h]   = log sum_j exp(scale * q[i,h,:] . K(j))          (natural log)
+ *
+ *   q            dev  [total_new_tokens, Hq, D]   requests back to back
+ *   k_pool       dev  [N, Hkv, S, D]              this layer's K pages
+ *   v_pool       dev  [N, Hkv, S, D]
+ *   block_tables dev  [batch, max_pages_per_req]  int32 logical -> physical page
+ *   prefix_lens  host [batch]  P_r >= 0, need not be a multiple of S
+ *   new_lens     host [batch]  C_r >= 0 (0 = the request has no rows)
+ *   out          dev  [total_new_tokens, Hq, D]   dtype of q, every row written
+ *   lse          dev  [total_new_tokens, Hq] fp32, or NULL
+ *   workspace    dev  >= mc_prefill_attn_workspace_bytes(...), 16-byte aligned;
+ *                     in use until the enqueued work has finished
+ *
+ * Token slots at or beyond P_r + C_r in a request's last page, and pages the
+ * block tables do not name, are never read as values (they may hold NaN).
+ * bf16: products on the matrix cores, fp32 accumulation and softmax, output
+ * rounded to nearest even.  f32: fp32 throughout.
+ * batch == 0 or total_new_tokens == 0 is MC_OK and enqueues nothing.
+ */
+mc_status mc_prefill_attn_paged(const mc_attn_params* p, const void* q, const void* k_pool,
+                                const void* v_pool, const int32_t* block_tables,
+                                int32_t max_pages_per_req, const int32_t* prefix_lens,
+                                const int32_t* new_lens, int32_t batch, void* out, float* lse,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Store path of layer-wise prefill (Section 5.2): gather pages of one layer's
+ * scattered pools into contiguous buffers, page i of the output = page
+ * page_ids[i] of the pool, bytes verbatim.
+ *
+ *   k_pool_layer, v_pool_layer  dev  num_pages * page_bytes each
+ *   page_ids                    dev  [n] int32 in [0, num_pages); duplicates allowed
+ *   k_out, v_out                dev  n * page_bytes each
+ *
+ * page_bytes must be a multiple of 16 and every pointer 16-byte aligned.
+ * n == 0 is MC_OK and enqueues nothing.
+ */
+mc_status mc_kv_pack_layer(const void* k_pool_layer, const void* v_pool_layer, int64_t num_pages,
+                           int64_t page_bytes, const int32_t* page_ids, int64_t n, void* k_out,
+                           void* v_out, void* hip_stream);
+
+/*
+ * Load path of layer-wise prefill (Section 5.2; Section 3 step 1): scatter
+ * contiguous buffers of n pages into the listed pages of one layer's pools,
+ * page page_ids[i] of the pool = page i of the input.  Pages not listed keep
+ * their bytes.  page_ids must be unique (duplicates: undefined which copy wins).
+ */
+mc_status mc_kv_unpack_layer(const void* k_in, const void* v_in, int64_t num_pages,
+                             int64_t page_bytes, const int32_t* page_ids, int64_t n,
+                             void* k_pool_layer, void* v_pool_layer, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MC_H_ */

@@ -1,0 +1,139 @@
+"""ctypes binding of ``libmooncake_hip.so``: argument marshalling only.
+
+Function names and argument order are those of ``include/mc.h``.  torch is used
+for device memory and streams; every step of the path runs in the library's
+kernels.  There is no fallback: if the library has not been built, loading
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG, "libmooncake_hip.so")
+
+MC_OK = 0
+MC_ERR_NULL, MC_ERR_SHAPE, MC_ERR_UNSUPPORTED, MC_ERR_ALIGN, MC_ERR_RANGE, MC_ERR_WORKSPACE, MC_ERR_HIP = range(1, 8)
+MC_DTYPE_BF16, MC_DTYPE_F32 = 0, 1
+
+EXPORTS = ("mc_status_string", "mc_prefill_attn_workspace_bytes", "mc_prefill_attn_paged",
+           "mc_kv_pack_layer", "mc_kv_unpack_layer")
+
+
+class McAttnParams(ctypes.Structure):
+    _fields_ = [("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32),
+                ("num_pages", ctypes.c_int64), ("dtype", ctypes.c_int32),
+                ("softmax_scale", ctypes.c_float)]
+
+
+class McError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: mc_status {status} ({status_string(status)})")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it was never built (run ``__graft_entry__.build()``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2407_00079_amd.build` "
+                               "(there is no CPU fallback)")
+        l = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        l.mc_status_string.restype = ctypes.c_char_p
+        l.mc_status_string.argtypes = [ctypes.c_int]
+        l.mc_prefill_attn_workspace_bytes.restype = ctypes.c_size_t
+        l.mc_prefill_attn_workspace_bytes.argtypes = [ctypes.POINTER(McAttnParams), i32, i64]
+        l.mc_prefill_attn_paged.restype = ctypes.c_int
+        l.mc_prefill_attn_paged.argtypes = [ctypes.POINTER(McAttnParams), vp, vp, vp, vp, i32, vp, vp, i32,
+                                            vp, vp, vp, ctypes.c_size_t, vp]
+        for f in (l.mc_kv_pack_layer, l.mc_kv_unpack_layer):
+            f.restype = ctypes.c_int
+            f.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, vp]
+        _lib = l
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().mc_status_string(int(status)).decode()
+
+
+def _dev_ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) or None
+
+
+def mc_prefill_attn_workspace_bytes(params: McAttnParams, batch: int, total_new_tokens: int) -> int:
+    return int(lib().mc_prefill_attn_workspace_bytes(ctypes.byref(params), batch, total_new_tokens))
+
+
+def mc_prefill_attn_paged_raw(params, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens,
+                              batch, out, lse, workspace, workspace_bytes, hip_stream) -> int:
+    """Plain-pointer call: every argument is an int address / ctypes object; returns the status."""
+    return int(lib().mc_prefill_attn_paged(ctypes.byref(params) if params is not None else None, q, k_pool, v_pool,
+                                           block_tables, max_pages_per_req, prefix_lens, new_lens, batch, out, lse,
+                                           workspace, workspace_bytes, hip_stream))
+
+
+def mc_prefill_attn_paged(params: McAttnParams, q, k_pool, v_pool, block_tables, prefix_lens, new_lens,
+                          out, lse=None, workspace=None, stream=None) -> None:
+    """Enqueue attention on ``stream`` (torch stream; default: current).
+
+    q, k_pool, v_pool, out: torch device tensors; block_tables: int32 device
+    tensor [batch, max_pages]; prefix_lens / new_lens: host sequences of ints;
+    workspace: uint8 device tensor of at least the size the library asks for.
+    """
+    batch = len(prefix_lens)
+    pl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in prefix_lens])
+    nl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in new_lens])
+    max_pages = int(block_tables.shape[1]) if block_tables is not None and block_tables.dim() == 2 else 0
+    ws_bytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    st = mc_prefill_attn_paged_raw(params, _dev_ptr(q), _dev_ptr(k_pool), _dev_ptr(v_pool), _dev_ptr(block_tables),
+                                   max_pages, ctypes.cast(pl, ctypes.c_void_p), ctypes.cast(nl, ctypes.c_void_p),
+                                   batch, _dev_ptr(out), _dev_ptr(lse), _dev_ptr(workspace), ws_bytes,
+                                   _stream_handle(stream))
+    if st != MC_OK:
+        raise McError(st, "mc_prefill_attn_paged")
+
+
+def mc_kv_pack_layer_raw(k_pool, v_pool, num_pages, page_bytes, page_ids, n, k_out, v_out, hip_stream) -> int:
+    return int(lib().mc_kv_pack_layer(k_pool, v_pool, num_pages, page_bytes, page_ids, n, k_out, v_out, hip_stream))
+
+
+def mc_kv_unpack_layer_raw(k_in, v_in, num_pages, page_bytes, page_ids, n, k_pool, v_pool, hip_stream) -> int:
+    return int(lib().mc_kv_unpack_layer(k_in, v_in, num_pages, page_bytes, page_ids, n, k_pool, v_pool, hip_stream))
+
+
+def mc_kv_pack_layer(k_pool_layer, v_pool_layer, num_pages: int, page_bytes: int, page_ids, n: int,
+                     k_out, v_out, stream=None) -> None:
+    st = mc_kv_pack_layer_raw(_dev_ptr(k_pool_layer), _dev_ptr(v_pool_layer), num_pages, page_bytes,
+                              _dev_ptr(page_ids), n, _dev_ptr(k_out), _dev_ptr(v_out), _stream_handle(stream))
+    if st != MC_OK:
+        raise McError(st, "mc_kv_pack_layer")
+
+
+def mc_kv_unpack_layer(k_in, v_in, num_pages: int, page_bytes: int, page_ids, n: int,
+                       k_pool_layer, v_pool_layer, stream=None) -> None:
+    st = mc_kv_unpack_layer_raw(_dev_ptr(k_in), _dev_ptr(v_in), num_pages, page_bytes, _dev_ptr(page_ids), n,
+                                _dev_ptr(k_pool_layer), _dev_ptr(v_pool_layer), _stream_handle(stream))
+    if st != MC_OK:
+        raise McError(st, "mc_kv_unpack_layer")
+
+
+def attn_params(num_q_heads: int, num_kv_heads: int, head_dim: int, page_size: int, num_pages: int,
+                dtype: str, softmax_scale: float = 0.0) -> McAttnParams:
+    return McAttnParams(num_q_heads, num_kv_heads, head_dim, page_size, num_pages,
+                        MC_DTYPE_BF16 if dtype == "bf16" else MC_DTYPE_F32, softmax_scale)

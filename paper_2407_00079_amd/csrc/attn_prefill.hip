@@ -1,0 +1,381 @@
+// Prefix-reused, paged, chunked-prefill attention for gfx950 (paper Section 3,
+// steps 1-2: the uncached tokens of a request attend to the reused prefix pages
+// plus their own pages; the paper gives no kernel, this design is ours).
+//
+// Shape of the computation
+//   * A workgroup (4 waves) owns a tile of stacked query rows of one (request,
+//     KV head): row = token * G + head_in_group, so a K/V tile staged once in
+//     LDS feeds all G query heads that share the KV head.
+//   * Scores are computed TRANSPOSED, S^T = K Q^T, on 32x32 MFMA tiles.  In the
+//     accumulator a lane then owns ONE query column (lane % 32) and 16 keys per
+//     32-key block, so the softmax row reductions are in-lane plus one exchange
+//     between the wave's halves, and exp2(S^T) is already laid out as the B
+//     operand of O^T += V^T P^T.  The key order inside that contraction is the
+//     accumulator's row order; V^T fragments are fetched in the same order with
+//     the LDS transpose read (bf16) or plain row reads (f32).
+//   * The KV loop walks the block table 64 keys (4 pages) at a time, double
+//     buffered in LDS.  Tiles that lie wholly inside what every row of the
+//     workgroup may see run a mask-free body; only tiles that touch the chunk's
+//     diagonal compare key index against row position.
+//   * Online softmax in fp32, base 2 (scale * log2 e folded into one fma).
+#include <type_traits>
+
+#include "mc_internal.h"
+
+namespace mc {
+namespace {
+
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#define MC_LDS __attribute__((address_space(3)))
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * 64;
+constexpr int kTileKeys = 64;          // keys per LDS tile = 4 pages of 16
+constexpr int kPageTokens = 16;
+constexpr int kRowBytes = 256;         // one K or V row: 128 bf16 or 64 f32
+constexpr int kPageHeadBytes = kPageTokens * kRowBytes;   // 4 KiB, contiguous in the pool
+constexpr int kTileBytes = kTileKeys * kRowBytes;         // 16 KiB
+constexpr int kPagesPerTile = kTileKeys / kPageTokens;
+
+// Combine a value with the one held by lane ^ 32.  v_permlane32_swap exchanges the upper
+// half of its first register with the lower half of its second, so after it every lane
+// holds its own value in one register and its partner's in the other; max and sum do not
+// care which is which.  Written as asm with two distinct read-write registers (the builtin
+// called with one value for both operands gets its two results merged by the optimiser);
+// the s_nop covers the VALU-write -> permlane read hazard the compiler cannot see.
+__device__ __forceinline__ void swap_halves(float& a, float& b) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float max_with_other_half(float x) {
+  float a = x, b = x;
+  swap_halves(a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float sum_with_other_half(float x) {
+  float a = x, b = x;
+  swap_halves(a, b);
+  return a + b;
+}
+
+// ---------------------------------------------------------------------------
+// dtype traits: how fragments are fetched and multiplied
+// ---------------------------------------------------------------------------
+struct Bf16 {
+  static constexpr int kD = 128;
+  static constexpr int kQKSteps = kD / 16;    // mfma 32x32x16 steps over head_dim
+  static constexpr int kPVSteps = 2;          // 16-key steps per 32-key block
+  static constexpr int kDBlocks = kD / 32;
+  typedef bf16x8 frag;
+
+  // 16-byte granule g of row `row` sits at granule g ^ swizzle(row)
+  static __device__ __forceinline__ int k_swz(int row) { return row & 15; }
+  static __device__ __forceinline__ int v_swz(int row) { return (row & 3) << 2; }
+
+  static __device__ __forceinline__ f32x16 mma(frag a, frag b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+  // B operand: Q[row][16*kk + 8*half .. +7]
+  static __device__ __forceinline__ frag load_q(const char* qrow, int kk, int half) {
+    return *reinterpret_cast<const frag*>(qrow + kk * 32 + half * 16);
+  }
+  // A operand: K[key][16*kk + 8*half .. +7], key = kb*32 + lane%32
+  static __device__ __forceinline__ frag load_k(const char* kt, int kb, int kk, int lane) {
+    const int row = kb * 32 + (lane & 31);
+    const int g = (kk * 2 + (lane >> 5)) ^ k_swz(row);
+    return *reinterpret_cast<const frag*>(kt + row * kRowBytes + g * 16);
+  }
+  // A operand of O^T += V^T P^T: V[key(e)][db*32 + lane%32] for the 8 keys
+  // 32*kb + 16*step + 8*(e/4) + 4*half + e%4, i.e. two groups of 4 consecutive keys.
+  // The transpose read returns, to lane i of a 16-lane group, element i%4 of lanes
+  // i/4, 4+i/4, 8+i/4, 12+i/4: source lane s must address key s/4, columns 4*(s%4)..+3.
+  static __device__ __forceinline__ frag load_v(const char* vt, int kb, int step, int db, int lane) {
+    const int half = lane >> 5;
+    const int s = lane & 15;
+    const int key0 = kb * 32 + step * 16 + half * 4 + (s >> 2);
+    const int col = db * 32 + ((lane >> 4) & 1) * 16 + (s & 3) * 4;   // element index, 8 per granule
+    const int g = col >> 3;
+    const int within = (col & 7) * 2;
+    const int off0 = key0 * kRowBytes + ((g ^ v_swz(key0)) * 16) + within;
+    const int key1 = key0 + 8;
+    const int off1 = key1 * kRowBytes + ((g ^ v_swz(key1)) * 16) + within;
+    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(vt + off0));
+    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(vt + off1));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+  // B operand: probabilities of accumulator registers 8*step .. 8*step+7
+  static __device__ __forceinline__ frag make_p(const f32x16& p, int step) {
+    frag f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = (__bf16)p[step * 8 + e];
+    return f;
+  }
+  // four consecutive output columns
+  static __device__ __forceinline__ void store4(char* orow, int col, float a, float b, float c, float d) {
+    bf16x4 v;
+    v[0] = (__bf16)a;
+    v[1] = (__bf16)b;
+    v[2] = (__bf16)c;
+    v[3] = (__bf16)d;
+    *reinterpret_cast<bf16x4*>(orow + col * 2) = v;
+  }
+};
+
+struct F32 {
+  static constexpr int kD = 64;
+  static constexpr int kQKSteps = kD / 2;     // mfma 32x32x2 steps over head_dim
+  static constexpr int kPVSteps = 16;         // one accumulator register (2 keys across halves) per step
+  static constexpr int kDBlocks = kD / 32;
+  typedef float frag;
+
+  static __device__ __forceinline__ int k_swz(int row) { return row & 15; }
+  static __device__ __forceinline__ int v_swz(int row) { return (row >> 2) & 1 ? 8 : 0; }
+
+  static __device__ __forceinline__ f32x16 mma(frag a, frag b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ frag load_q(const char* qrow, int kk, int half) {
+    return *reinterpret_cast<const float*>(qrow + (kk * 2 + half) * 4);
+  }
+  static __device__ __forceinline__ frag load_k(const char* kt, int kb, int kk, int lane) {
+    const int row = kb * 32 + (lane & 31);
+    const int col = kk * 2 + (lane >> 5);
+    const int g = (col >> 2) ^ k_swz(row);
+    return *reinterpret_cast<const float*>(kt + row * kRowBytes + g * 16 + (col & 3) * 4);
+  }
+  // step = accumulator register r: key 32*kb + 8*(r/4) + 4*half + r%4, column db*32 + lane%32
+  static __device__ __forceinline__ frag load_v(const char* vt, int kb, int step, int db, int lane) {
+    const int key = kb * 32 + (step >> 2) * 8 + (lane >> 5) * 4 + (step & 3);
+    const int col = db * 32 + (lane & 31);
+    const int g = (col >> 2) ^ v_swz(key);
+    return *reinterpret_cast<const float*>(vt + key * kRowBytes + g * 16 + (col & 3) * 4);
+  }
+  static __device__ __forceinline__ frag make_p(const f32x16& p, int step) { return p[step]; }
+  static __device__ __forceinline__ void store4(char* orow, int col, float a, float b, float c, float d) {
+    f32x4 v = {a, b, c, d};
+    *reinterpret_cast<f32x4*>(orow + col * 4) = v;
+  }
+};
+
+// ---------------------------------------------------------------------------
+// kernel
+// ---------------------------------------------------------------------------
+template <class T, int QB>
+__global__ __launch_bounds__(kThreads) void attn_prefill_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) char smem[4 * kTileBytes];   // K0 V0 K1 V1
+  constexpr int kTileRows = kWaves * QB * 32;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int half = lane >> 5;
+
+  const AttnItem item = a.items[blockIdx.x];
+  const AttnReq rq = a.reqs[item.req];
+  const int G = a.G;
+  const int P = rq.prefix;
+  const int L = rq.prefix + rq.chunk;
+  const int n_rows = rq.chunk * G;
+  const int32_t* __restrict__ bt = a.block_tables + (int64_t)item.req * a.max_pages;
+  const int last_page = rq.pages - 1;
+
+  // ---- this lane's query rows: Q fragments stay in registers for the whole KV loop
+  typename T::frag qf[QB][T::kQKSteps];
+  int tok[QB];      // token index inside the chunk
+  int qhead[QB];
+  bool live[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    int row = item.row0 + (wave * QB + qb) * 32 + (lane & 31);
+    live[qb] = row < n_rows;
+    row = live[qb] ? row : n_rows - 1;          // dead rows recompute the last row, never stored
+    tok[qb] = row / G;
+    qhead[qb] = item.kv_head * G + (row - tok[qb] * G);
+    const char* qrow = reinterpret_cast<const char*>(a.q) +
+                       ((int64_t)(rq.q_off + tok[qb]) * a.Hq + qhead[qb]) * kRowBytes;
+#pragma unroll
+    for (int kk = 0; kk < T::kQKSteps; ++kk) qf[qb][kk] = T::load_q(qrow, kk, half);
+  }
+
+  // ---- keys this workgroup needs, and how many leading tiles need no mask
+  const int tok_first = item.row0 / G;
+  int tok_last = (item.row0 + kTileRows - 1) / G;
+  tok_last = tok_last < rq.chunk - 1 ? tok_last : rq.chunk - 1;
+  const int kv_end = P + tok_last + 1;                       // <= L
+  const int n_tiles = (kv_end + kTileKeys - 1) / kTileKeys;
+  int n_free = (P + tok_first + 1) / kTileKeys;              // every key of these tiles is visible to every row
+  n_free = n_free < n_tiles ? n_free : n_tiles;
+
+  // ---- global -> register -> LDS staging: thread copies 16 bytes of each of the tile's 4 pages
+  const char* kbase = reinterpret_cast<const char*>(a.k_pool) + (int64_t)item.kv_head * kPageHeadBytes + tid * 16;
+  const char* vbase = reinterpret_cast<const char*>(a.v_pool) + (int64_t)item.kv_head * kPageHeadBytes + tid * 16;
+  const int64_t page_stride = (int64_t)a.Hkv * kPageHeadBytes;
+  u32x4 kreg[kPagesPerTile], vreg[kPagesPerTile];
+
+  auto fetch = [&](int tile) {
+#pragma unroll
+    for (int p = 0; p < kPagesPerTile; ++p) {
+      int lp = tile * kPagesPerTile + p;
+      lp = lp < last_page ? lp : last_page;                  // never index the table past the request's pages
+      const int64_t off = (int64_t)bt[lp] * page_stride;
+      kreg[p] = *reinterpret_cast<const u32x4*>(kbase + off);
+      vreg[p] = *reinterpret_cast<const u32x4*>(vbase + off);
+    }
+  };
+  auto stage = [&](int tile, int buf) {
+    char* kt = smem + buf * 2 * kTileBytes;
+    char* vt = kt + kTileBytes;
+#pragma unroll
+    for (int p = 0; p < kPagesPerTile; ++p) {
+      const int row = p * kPageTokens + (tid >> 4);
+      const int g = tid & 15;
+      // slots at or past the request's length may hold anything: store zeros instead
+      const bool in_seq = tile * kTileKeys + row < L;
+      const u32x4 zero = {0, 0, 0, 0};
+      *reinterpret_cast<u32x4*>(kt + row * kRowBytes + ((g ^ T::k_swz(row)) * 16)) = in_seq ? kreg[p] : zero;
+      *reinterpret_cast<u32x4*>(vt + row * kRowBytes + ((g ^ T::v_swz(row)) * 16)) = in_seq ? vreg[p] : zero;
+    }
+  };
+
+  // ---- running softmax state and output accumulators (O^T: registers index head_dim)
+  f32x16 o[QB][T::kDBlocks];
+  float m_run[QB], l_run[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    m_run[qb] = -INFINITY;
+    l_run[qb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < T::kDBlocks; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
+  }
+  const float c = a.scale_log2e;
+
+  auto compute = [&](int tile, int buf, auto masked_tag) {
+    constexpr bool kMasked = decltype(masked_tag)::value;
+    const char* kt = smem + buf * 2 * kTileBytes;
+    const char* vt = kt + kTileBytes;
+    // S^T = K Q^T
+    f32x16 s[QB][2];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[qb][kb][r] = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int kk = 0; kk < T::kQKSteps; ++kk) {
+        const typename T::frag kf = T::load_k(kt, kb, kk, lane);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) s[qb][kb] = T::mma(kf, qf[qb][kk], s[qb][kb]);
+      }
+    // online softmax per query column
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      if (kMasked) {
+        // key of register r in block kb: tile*64 + kb*32 + 8*(r/4) + 4*half + r%4; visible iff <= P + tok
+        const int lim = P + tok[qb] - tile * kTileKeys - half * 4;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            s[qb][kb][r] = (kb * 32 + (r >> 2) * 8 + (r & 3) <= lim) ? s[qb][kb][r] : -INFINITY;
+      }
+      float mx = s[qb][0][0];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[qb][kb][r]);
+      mx = max_with_other_half(mx);
+      const float m_new = fmaxf(m_run[qb], mx * c);
+      const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+      float sum = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kb][r], c, -m_new));
+          s[qb][kb][r] = p;
+          sum += p;
+        }
+      sum = sum_with_other_half(sum);
+      l_run[qb] = l_run[qb] * alpha + sum;
+      m_run[qb] = m_new;
+#pragma unroll
+      for (int db = 0; db < T::kDBlocks; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
+    }
+    // O^T += V^T P^T
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int st = 0; st < T::kPVSteps; ++st) {
+        typename T::frag pf[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) pf[qb] = T::make_p(s[qb][kb], st);
+#pragma unroll
+        for (int db = 0; db < T::kDBlocks; ++db) {
+          const typename T::frag vf = T::load_v(vt, kb, st, db, lane);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) o[qb][db] = T::mma(vf, pf[qb], o[qb][db]);
+        }
+      }
+  };
+
+  // ---- KV loop, double buffered
+  fetch(0);
+  stage(0, 0);
+  __syncthreads();
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    const int buf = tile & 1;
+    const bool more = tile + 1 < n_tiles;
+    if (more) fetch(tile + 1);
+    if (tile < n_free)
+      compute(tile, buf, std::false_type{});
+    else
+      compute(tile, buf, std::true_type{});
+    if (more) stage(tile + 1, buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: normalise, round, store; lane holds 4 consecutive columns per (db, r/4)
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    if (!live[qb]) continue;
+    const float inv = 1.0f / l_run[qb];
+    const int64_t orow_idx = (int64_t)(rq.q_off + tok[qb]) * a.Hq + qhead[qb];
+    char* orow = reinterpret_cast<char*>(a.out) + orow_idx * kRowBytes;
+#pragma unroll
+    for (int db = 0; db < T::kDBlocks; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int col = db * 32 + q4 * 8 + half * 4;
+        T::store4(orow, col, o[qb][db][q4 * 4 + 0] * inv, o[qb][db][q4 * 4 + 1] * inv,
+                  o[qb][db][q4 * 4 + 2] * inv, o[qb][db][q4 * 4 + 3] * inv);
+      }
+    if (a.lse != nullptr && half == 0)
+      a.lse[orow_idx] = (m_run[qb] + __builtin_amdgcn_logf(l_run[qb])) * 0.6931471805599453f;
+  }
+}
+
+}  // namespace
+
+int attn_tile_rows(int dtype) { return dtype == MC_DTYPE_BF16 ? kWaves * 1 * 32 : kWaves * 1 * 32; }
+
+hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream) {
+  if (dtype == MC_DTYPE_BF16)
+    attn_prefill_kernel<Bf16, 1><<<args.n_items, kThreads, 0, stream>>>(args);
+  else
+    attn_prefill_kernel<F32, 1><<<args.n_items, kThreads, 0, stream>>>(args);
+  return hipGetLastError();
+}
+
+}  // namespace mc

@@ -1,0 +1,262 @@
+// C-ABI front end: host-side validation, work-list construction, launches.
+// Every check runs before the first HIP call, so a rejected call leaves no trace.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "mc_internal.h"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+mc_status check_params(const mc_attn_params* p) {
+  if (p == nullptr) return MC_ERR_NULL;
+  if (p->num_q_heads <= 0 || p->num_kv_heads <= 0 || p->head_dim <= 0 || p->page_size <= 0 || p->num_pages <= 0)
+    return MC_ERR_SHAPE;
+  if (p->num_q_heads % p->num_kv_heads != 0) return MC_ERR_SHAPE;
+  if (p->dtype != MC_DTYPE_BF16 && p->dtype != MC_DTYPE_F32) return MC_ERR_UNSUPPORTED;
+  if (p->page_size != 16) return MC_ERR_UNSUPPORTED;
+  if (p->dtype == MC_DTYPE_BF16 && p->head_dim != 128) return MC_ERR_UNSUPPORTED;
+  if (p->dtype == MC_DTYPE_F32 && p->head_dim != 64) return MC_ERR_UNSUPPORTED;
+  if (!(p->softmax_scale >= 0.f) || std::isinf(p->softmax_scale)) return MC_ERR_SHAPE;
+  return MC_OK;
+}
+
+// upper bound on work items: per request and KV head, ceil(C_r * G / rows) <= C_r * G / rows + 1
+size_t max_items(const mc_attn_params* p, int32_t batch, int64_t total_new_tokens) {
+  const int64_t rows = mc::attn_tile_rows(p->dtype);
+  const int64_t G = p->num_q_heads / p->num_kv_heads;
+  return (size_t)(p->num_kv_heads * ((total_new_tokens * G) / rows + batch));
+}
+
+// Pinned host slots the work list is written to before its asynchronous upload.  A slot is
+// reused only after the event recorded behind its last upload has completed, so calls never
+// wait for the stream's earlier work and the host copy outlives the transfer.  Host memory
+// only; grows to the largest work list seen and is kept until the process ends.
+class StagingRing {
+ public:
+  // returns a slot with at least `bytes` of pinned memory, or nullptr if HIP refuses
+  void* acquire(size_t bytes, int* slot_out) {
+    std::lock_guard<std::mutex> lock(mu_);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    Slot& s = slots_[next_];
+    if (s.ev != nullptr && s.dev == dev) {
+      if (s.busy && hipEventSynchronize(s.ev) != hipSuccess) return nullptr;
+    } else {
+      // first use, or the slot belongs to another device: rebuild it for this one
+      if (s.ev != nullptr) {
+        (void)hipEventSynchronize(s.ev);
+        (void)hipEventDestroy(s.ev);
+        s.ev = nullptr;
+      }
+      if (hipEventCreateWithFlags(&s.ev, hipEventDisableTiming) != hipSuccess) return nullptr;
+      s.dev = dev;
+    }
+    s.busy = false;
+    if (s.cap < bytes) {
+      if (s.host != nullptr) (void)hipHostFree(s.host);
+      s.host = nullptr;
+      s.cap = 0;
+      const size_t want = std::max<size_t>(bytes, 1 << 16);
+      if (hipHostMalloc(&s.host, want, hipHostMallocDefault) != hipSuccess) return nullptr;
+      s.cap = want;
+    }
+    *slot_out = next_;
+    next_ = (next_ + 1) % kSlots;
+    return s.host;
+  }
+  bool release_after(int slot, hipStream_t stream) {
+    std::lock_guard<std::mutex> lock(mu_);
+    Slot& s = slots_[slot];
+    if (hipEventRecord(s.ev, stream) != hipSuccess) return false;
+    s.busy = true;
+    return true;
+  }
+
+ private:
+  static constexpr int kSlots = 8;
+  struct Slot {
+    void* host = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;
+    int dev = -1;
+    bool busy = false;
+  };
+  std::mutex mu_;
+  Slot slots_[kSlots];
+  int next_ = 0;
+};
+
+StagingRing g_staging;
+
+}  // namespace
+
+extern "C" {
+
+const char* mc_status_string(mc_status s) {
+  switch (s) {
+    case MC_OK: return "ok";
+    case MC_ERR_NULL: return "null pointer";
+    case MC_ERR_SHAPE: return "bad shape";
+    case MC_ERR_UNSUPPORTED: return "unsupported head_dim / page_size / dtype";
+    case MC_ERR_ALIGN: return "misaligned pointer or page size";
+    case MC_ERR_RANGE: return "size out of range";
+    case MC_ERR_WORKSPACE: return "workspace missing or too small";
+    case MC_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+size_t mc_prefill_attn_workspace_bytes(const mc_attn_params* p, int32_t batch, int64_t total_new_tokens) {
+  if (check_params(p) != MC_OK || batch < 0 || total_new_tokens < 0) return 0;
+  return sizeof(mc::AttnItem) * max_items(p, batch, total_new_tokens) + sizeof(mc::AttnReq) * (size_t)batch + 64;
+}
+
+mc_status mc_prefill_attn_paged(const mc_attn_params* p, const void* q, const void* k_pool, const void* v_pool,
+                                const int32_t* block_tables, int32_t max_pages_per_req,
+                                const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch, void* out,
+                                float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  mc_status st = check_params(p);
+  if (st != MC_OK) return st;
+  if (batch < 0 || max_pages_per_req < 0) return MC_ERR_SHAPE;
+  if (batch == 0) return MC_OK;
+  if (prefix_lens == nullptr || new_lens == nullptr) return MC_ERR_NULL;
+
+  int64_t total_new = 0;
+  for (int32_t r = 0; r < batch; ++r) {
+    if (prefix_lens[r] < 0 || new_lens[r] < 0) return MC_ERR_SHAPE;
+    const int64_t len = (int64_t)prefix_lens[r] + new_lens[r];
+    if (len > INT32_MAX - 1024) return MC_ERR_RANGE;
+    if (new_lens[r] > 0 && (int64_t)max_pages_per_req * p->page_size < len) return MC_ERR_SHAPE;
+    total_new += new_lens[r];
+  }
+  if (total_new == 0) return MC_OK;
+  if (q == nullptr || k_pool == nullptr || v_pool == nullptr || block_tables == nullptr || out == nullptr)
+    return MC_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out) || !aligned16(workspace) ||
+      (reinterpret_cast<uintptr_t>(block_tables) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+    return MC_ERR_ALIGN;
+  const int G = p->num_q_heads / p->num_kv_heads;
+  if (total_new * p->num_q_heads > INT32_MAX || (int64_t)batch * max_pages_per_req > INT32_MAX) return MC_ERR_RANGE;
+  if (workspace == nullptr || workspace_bytes < mc_prefill_attn_workspace_bytes(p, batch, total_new))
+    return MC_ERR_WORKSPACE;
+
+  // ---- work list: one item per (request, KV head, tile of stacked rows), most keys first,
+  //      dealt round-robin so that consecutive workgroup ids (which land on different XCDs)
+  //      take different (request, KV head) streams and each XCD's L2 keeps one stream hot
+  const int rows = mc::attn_tile_rows(p->dtype);
+  std::vector<mc::AttnReq> reqs((size_t)batch);
+  struct Keyed {
+    int64_t cost;
+    mc::AttnItem it;
+  };
+  constexpr int kXcd = 8;
+  std::vector<Keyed> lanes[kXcd];
+  int64_t q_off = 0;
+  for (int32_t r = 0; r < batch; ++r) {
+    const int32_t P = prefix_lens[r], C = new_lens[r];
+    reqs[(size_t)r] = {(int32_t)q_off, P, C, (int32_t)(((int64_t)P + C + p->page_size - 1) / p->page_size)};
+    q_off += C;
+    const int64_t n_rows = (int64_t)C * G;
+    for (int32_t g = 0; g < p->num_kv_heads; ++g)
+      for (int64_t row0 = 0; row0 < n_rows; row0 += rows) {
+        const int64_t tok_last = std::min<int64_t>(C - 1, (row0 + rows - 1) / G);
+        lanes[(r * p->num_kv_heads + g) % kXcd].push_back({P + tok_last + 1, {r, g, (int32_t)row0, 0}});
+      }
+  }
+  std::vector<mc::AttnItem> items;
+  size_t n_items = 0;
+  for (auto& l : lanes) {
+    std::stable_sort(l.begin(), l.end(), [](const Keyed& a, const Keyed& b) { return a.cost > b.cost; });
+    n_items += l.size();
+  }
+  items.reserve(n_items);
+  {
+    size_t cur[kXcd] = {0};
+    int x = 0;
+    while (items.size() < n_items) {
+      // next non-empty lane, starting from the one whose turn it is
+      int tries = 0;
+      while (cur[x] >= lanes[x].size() && tries < kXcd) {
+        x = (x + 1) % kXcd;
+        ++tries;
+      }
+      items.push_back(lanes[x][cur[x]++].it);
+      x = (x + 1) % kXcd;
+    }
+  }
+
+  // ---- upload work list + request table into the caller's workspace (one pinned, async copy)
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  char* ws = reinterpret_cast<char*>(workspace);
+  const size_t items_bytes = sizeof(mc::AttnItem) * n_items;
+  const size_t reqs_off = (items_bytes + 15) & ~(size_t)15;
+  const size_t up_bytes = reqs_off + sizeof(mc::AttnReq) * reqs.size();
+  int slot = -1;
+  char* host = reinterpret_cast<char*>(g_staging.acquire(up_bytes, &slot));
+  if (host == nullptr) return MC_ERR_HIP;
+  std::memcpy(host, items.data(), items_bytes);
+  std::memcpy(host + reqs_off, reqs.data(), sizeof(mc::AttnReq) * reqs.size());
+  if (hipMemcpyAsync(ws, host, up_bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
+  if (!g_staging.release_after(slot, stream)) return MC_ERR_HIP;
+
+  mc::AttnArgs args;
+  args.q = q;
+  args.k_pool = k_pool;
+  args.v_pool = v_pool;
+  args.block_tables = block_tables;
+  args.out = out;
+  args.lse = lse;
+  args.items = reinterpret_cast<const mc::AttnItem*>(ws);
+  args.reqs = reinterpret_cast<const mc::AttnReq*>(ws + reqs_off);
+  args.Hq = p->num_q_heads;
+  args.Hkv = p->num_kv_heads;
+  args.G = G;
+  args.max_pages = max_pages_per_req;
+  const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale : 1.0 / std::sqrt((double)p->head_dim);
+  args.scale_log2e = (float)(scale * 1.4426950408889634);
+  args.n_items = (int32_t)n_items;
+  if (mc::launch_attn(p->dtype, args, stream) != hipSuccess) return MC_ERR_HIP;
+  return MC_OK;
+}
+
+static mc_status check_copy(const void* a, const void* b, int64_t num_pages, int64_t page_bytes, const int32_t* ids,
+                            int64_t n, const void* c, const void* d) {
+  if (num_pages < 0 || page_bytes < 0 || n < 0) return MC_ERR_SHAPE;
+  if (page_bytes % 16 != 0) return MC_ERR_ALIGN;
+  if (n == 0 || page_bytes == 0) return MC_OK;
+  if (a == nullptr || b == nullptr || c == nullptr || d == nullptr || ids == nullptr) return MC_ERR_NULL;
+  if (num_pages == 0) return MC_ERR_SHAPE;
+  if (!aligned16(a) || !aligned16(b) || !aligned16(c) || !aligned16(d) || (reinterpret_cast<uintptr_t>(ids) & 3u))
+    return MC_ERR_ALIGN;
+  const int64_t slices = (page_bytes / 16 + 1023) / 1024;
+  if (n > INT32_MAX || n * slices > INT32_MAX) return MC_ERR_RANGE;
+  return MC_OK;
+}
+
+mc_status mc_kv_pack_layer(const void* k_pool_layer, const void* v_pool_layer, int64_t num_pages, int64_t page_bytes,
+                           const int32_t* page_ids, int64_t n, void* k_out, void* v_out, void* hip_stream) {
+  mc_status st = check_copy(k_pool_layer, v_pool_layer, num_pages, page_bytes, page_ids, n, k_out, v_out);
+  if (st != MC_OK || n == 0 || page_bytes == 0) return st;
+  if (mc::launch_kv_copy(true, k_pool_layer, v_pool_layer, k_out, v_out, page_ids, n, page_bytes,
+                         reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return MC_ERR_HIP;
+  return MC_OK;
+}
+
+mc_status mc_kv_unpack_layer(const void* k_in, const void* v_in, int64_t num_pages, int64_t page_bytes,
+                             const int32_t* page_ids, int64_t n, void* k_pool_layer, void* v_pool_layer,
+                             void* hip_stream) {
+  mc_status st = check_copy(k_in, v_in, num_pages, page_bytes, page_ids, n, k_pool_layer, v_pool_layer);
+  if (st != MC_OK || n == 0 || page_bytes == 0) return st;
+  if (mc::launch_kv_copy(false, k_in, v_in, k_pool_layer, v_pool_layer, page_ids, n, page_bytes,
+                         reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return MC_ERR_HIP;
+  return MC_OK;
+}
+
+}  // extern "C"

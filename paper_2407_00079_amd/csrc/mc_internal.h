@@ -1,0 +1,51 @@
+// Internal declarations shared by the C-ABI front end and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mc.h"
+
+namespace mc {
+
+// One unit of attention work: a tile of stacked query rows of one (request, KV head).
+// Stacked row index = token_in_chunk * G + head_in_group, so one K/V tile in LDS
+// feeds all G query heads of the group.
+struct AttnItem {
+  int32_t req;
+  int32_t kv_head;
+  int32_t row0;  // first stacked row of the tile
+  int32_t pad;
+};
+
+struct AttnReq {
+  int32_t q_off;   // index of the request's first new token in q / out
+  int32_t prefix;  // P_r
+  int32_t chunk;   // C_r
+  int32_t pages;   // ceil((P_r + C_r) / S): entries of the block-table row that may be read
+};
+
+struct AttnArgs {
+  const void* q;
+  const void* k_pool;
+  const void* v_pool;
+  const int32_t* block_tables;
+  void* out;
+  float* lse;
+  const AttnItem* items;
+  const AttnReq* reqs;
+  int32_t Hq, Hkv, G, max_pages;
+  float scale_log2e;  // softmax scale * log2(e): scores go through exp2
+  int32_t n_items;
+};
+
+// rows of stacked queries one workgroup covers, per dtype (host needs it to cut the work list)
+int attn_tile_rows(int dtype);
+
+// enqueue the attention kernel over args.n_items work items
+hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream);
+
+// enqueue gather (pack) or scatter (unpack) of n pages of page_bytes for K and V
+hipError_t launch_kv_copy(bool pack, const void* k_src, const void* v_src, void* k_dst, void* v_dst,
+                          const int32_t* page_ids, int64_t n, int64_t page_bytes, hipStream_t stream);
+
+}  // namespace mc

@@ -1,0 +1,91 @@
+"""GPU parity: mc_kv_pack_layer / mc_kv_unpack_layer against the CPU oracle, byte for byte."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_00079_amd import binding as B
+from paper_2407_00079_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+@pytest.mark.parametrize("page_bytes,n,N,N2,layers", [
+    (4096, 24, 64, 64, 2),          # the tiny configuration: fp32, 1 KV head, head_dim 64
+    (32768, 300, 512, 700, 2),      # LLaMA2-70B page: 16 tokens x 8 KV heads x 128 x bf16
+    (16, 5, 8, 8, 1),               # smallest legal page
+    (16400, 37, 64, 80, 1),         # ragged: one full slice + a 16-byte tail
+    (49152, 33, 40, 40, 1),         # three slices
+    (4096, 1, 1, 1, 1),
+])
+def test_pack_unpack_match_oracle(oracle, page_bytes, n, N, N2, layers):
+    pc = W.make_pack_case(1234 + n, layers, N, N2, page_bytes, n)
+    ids = _dev(pc.src_ids)
+    ids2 = _dev(pc.dst_ids)
+    rng = np.random.default_rng(9)
+    for l in range(layers):
+        print(f"pack case page_bytes={page_bytes} n={n} layer={l}", flush=True)
+        kp, vp = _dev(pc.k_pools[l]), _dev(pc.v_pools[l])
+        k_out = torch.zeros((n, page_bytes), dtype=torch.uint8, device="cuda:0")
+        v_out = torch.zeros_like(k_out)
+        B.mc_kv_pack_layer(kp, vp, N, page_bytes, ids, n, k_out, v_out)
+        k_ref, v_ref = oracle.kv_pack_layer(pc.k_pools[l], pc.v_pools[l], pc.src_ids)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(k_out.cpu().numpy(), k_ref)
+        np.testing.assert_array_equal(v_out.cpu().numpy(), v_ref)
+
+        k2_host = rng.integers(0, 256, size=(N2, page_bytes), dtype=np.uint8)
+        v2_host = rng.integers(0, 256, size=(N2, page_bytes), dtype=np.uint8)
+        k2, v2 = _dev(k2_host), _dev(v2_host)
+        B.mc_kv_unpack_layer(k_out, v_out, N2, page_bytes, ids2, n, k2, v2)
+        oracle.kv_unpack_layer(k_ref, v_ref, pc.dst_ids, k2_host, v2_host)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(k2.cpu().numpy(), k2_host)      # listed pages moved, others untouched
+        np.testing.assert_array_equal(v2.cpu().numpy(), v2_host)
+
+
+def test_pack_with_duplicate_ids(oracle):
+    pc = W.make_pack_case(77, 1, 8, 64, 4096, 40, unique_src=False)
+    kp, vp, ids = _dev(pc.k_pools[0]), _dev(pc.v_pools[0]), _dev(pc.src_ids)
+    k_out = torch.zeros((40, 4096), dtype=torch.uint8, device="cuda:0")
+    v_out = torch.zeros_like(k_out)
+    B.mc_kv_pack_layer(kp, vp, 8, 4096, ids, 40, k_out, v_out)
+    k_ref, v_ref = oracle.kv_pack_layer(pc.k_pools[0], pc.v_pools[0], pc.src_ids)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(k_out.cpu().numpy(), k_ref)
+    np.testing.assert_array_equal(v_out.cpu().numpy(), v_ref)
+
+
+def test_round_trip_at_full_layer_size_on_a_side_stream(oracle):
+    """One layer of the streaming configuration (2048 pages of 32 KiB), on a non-default stream."""
+    sh = W.config_shapes(5)
+    pc = W.make_pack_case(sh["seed"], 1, sh["num_pages"], sh["num_pages_dst"], sh["page_bytes"], sh["n"])
+    n, pb = sh["n"], sh["page_bytes"]
+    kp, vp = _dev(pc.k_pools[0]), _dev(pc.v_pools[0])
+    ids, ids2 = _dev(pc.src_ids), _dev(pc.dst_ids)
+    k_lin = torch.empty((n, pb), dtype=torch.uint8, device="cuda:0")
+    v_lin = torch.empty_like(k_lin)
+    k2 = torch.zeros((sh["num_pages_dst"], pb), dtype=torch.uint8, device="cuda:0")
+    v2 = torch.zeros_like(k2)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        B.mc_kv_pack_layer(kp, vp, sh["num_pages"], pb, ids, n, k_lin, v_lin, side)
+        B.mc_kv_unpack_layer(k_lin, v_lin, sh["num_pages_dst"], pb, ids2, n, k2, v2, side)
+    side.synchronize()
+    k_ref, v_ref = oracle.kv_pack_layer(pc.k_pools[0], pc.v_pools[0], pc.src_ids, threads=8)
+    np.testing.assert_array_equal(k_lin.cpu().numpy(), k_ref)
+    np.testing.assert_array_equal(v_lin.cpu().numpy(), v_ref)
+    k2h, v2h = k2.cpu().numpy(), v2.cpu().numpy()
+    np.testing.assert_array_equal(k2h[pc.dst_ids], pc.k_pools[0][pc.src_ids])
+    np.testing.assert_array_equal(v2h[pc.dst_ids], pc.v_pools[0][pc.src_ids])
+    rest = np.setdiff1d(np.arange(sh["num_pages_dst"]), pc.dst_ids)
+    assert not k2h[rest].any() and not v2h[rest].any()
+
+
+def test_empty_list_is_a_noop():
+    B.mc_kv_pack_layer(None, None, 8, 4096, None, 0, None, None)
+    B.mc_kv_unpack_layer(None, None, 8, 4096, None, 0, None, None)
