@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the KVCache-reuse hot path on one MI355X.
+
+One step = one layer of layer-wise prefill (paper Section 5.2) on two HIP streams:
+  copy stream:    mc_kv_unpack_layer(l)  (load the layer's KV pages into the paged pool)
+  compute stream: wait load(l) -> mc_prefill_attn_paged (the attention workload)
+  copy stream:    wait attention(l) -> mc_kv_pack_layer(l)  (store the layer's pages)
+The attention workload is configuration 2 (64/8 heads, head_dim 128, bf16, 8192 reused
+prefix tokens + 8192 new tokens); the page traffic is one layer of configuration 5
+(2048 pages of 32 KiB for K and for V, each direction).  Inputs are seeded synthetic
+tensors, resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is attention TFLOP/s over the whole timed region
+(visible query-key pairs only, both contractions), with the page traffic overlapped.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2516.6   # 256 CU x 4 SIMD x 1024 flop/cycle x 2.4 GHz
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--attn-config", type=int, default=2, choices=(2, 3, 4),
+                    help="attention workload of the step (default: configuration 2)")
+    ap.add_argument("--layers", type=int, default=8, help="distinct per-layer pools the steps cycle through")
+    ap.add_argument("--cpu-rows", type=int, default=12288, help="rows the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the isolated / configuration-3 measurements")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import numpy as np
+    import torch
+    from paper_2407_00079_amd import binding as B
+    from paper_2407_00079_amd import workloads as W
+
+    B.lib()   # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    K, Wm = args.steps, args.warmup
+
+    def to_dev(a):
+        a = np.ascontiguousarray(a)
+        return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
+
+    class Attn:
+        def __init__(self, idx):
+            self.idx = idx
+            self.case = W.make_config_attn(idx, poison=False)
+            c = self.case
+            self.q, self.k, self.v, self.bt = to_dev(c.q), to_dev(c.k_pool), to_dev(c.v_pool), to_dev(c.block_tables)
+            self.params = B.attn_params(c.num_q_heads, c.num_kv_heads, c.head_dim, c.page_size, c.num_pages, c.dtype)
+            self.ws = torch.empty(B.mc_prefill_attn_workspace_bytes(self.params, c.batch, c.total_new),
+                                  dtype=torch.uint8, device=dev)
+            self.out = torch.empty(c.q.shape, dtype=torch.bfloat16, device=dev)
+            self.lse = torch.empty((c.total_new, c.num_q_heads), dtype=torch.float32, device=dev)
+            self.pl, self.nl = c.prefix_lens.tolist(), c.new_lens.tolist()
+            self.flops = c.flops()
+
+        def launch(self, stream):
+            B.mc_prefill_attn_paged(self.params, self.q, self.k, self.v, self.bt, self.pl, self.nl, self.out,
+                                    self.lse, self.ws, stream)
+
+        def time_isolated(self, iters=10, warm=3):
+            s = torch.cuda.current_stream()
+            for _ in range(warm):
+                self.launch(s)
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+            for a, b in ev:
+                a.record(s)
+                self.launch(s)
+                b.record(s)
+            torch.cuda.synchronize()
+            ms = sorted(a.elapsed_time(b) for a, b in ev)
+            return ms[len(ms) // 2], ms[0]
+
+    attn = Attn(args.attn_config)
+
+    # ---- one layer's page traffic (configuration 5), `layers` distinct pool sets so steps do not hit in cache
+    sh = W.config_shapes(5)
+    n, pb, N1, N2 = sh["n"], sh["page_bytes"], sh["num_pages"], sh["num_pages_dst"]
+    rng = np.random.default_rng(sh["seed"])
+    src_ids = to_dev(rng.permutation(N1)[:n].astype(np.int32))
+    dst_ids = to_dev(rng.permutation(N2)[:n].astype(np.int32))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(sh["seed"])
+    LAY = args.layers
+    # remote (contiguous) copies to load from, pools to load into / store from, contiguous buffers to store to
+    k_remote = torch.randint(0, 256, (LAY, n, pb), dtype=torch.uint8, device=dev, generator=gen)
+    v_remote = torch.randint(0, 256, (LAY, n, pb), dtype=torch.uint8, device=dev, generator=gen)
+    k_pool = torch.randint(0, 256, (LAY, N2, pb), dtype=torch.uint8, device=dev, generator=gen)
+    v_pool = torch.randint(0, 256, (LAY, N2, pb), dtype=torch.uint8, device=dev, generator=gen)
+    k_store = torch.empty((LAY, n, pb), dtype=torch.uint8, device=dev)
+    v_store = torch.empty((LAY, n, pb), dtype=torch.uint8, device=dev)
+    copy_bytes = 2 * 2 * n * pb          # read + write, K and V, one direction
+
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def unpack(l, stream):
+        B.mc_kv_unpack_layer(k_remote[l], v_remote[l], N2, pb, dst_ids, n, k_pool[l], v_pool[l], stream)
+
+    def pack(l, stream):
+        B.mc_kv_pack_layer(k_pool[l], v_pool[l], N2, pb, dst_ids, n, k_store[l], v_store[l], stream)
+
+    def run_steps(count, timed):
+        """Layer-wise schedule: load(l+1) is in flight while attention(l) runs; store(l) follows attention(l)."""
+        marks = []
+        loaded = [torch.cuda.Event() for _ in range(count + 1)]
+        attended = [torch.cuda.Event() for _ in range(count)]
+        with torch.cuda.stream(copy):
+            unpack(0, copy)
+            loaded[0].record(copy)
+        for i in range(count):
+            l = i % LAY
+            with torch.cuda.stream(copy):
+                if i + 1 < count:
+                    unpack((i + 1) % LAY, copy)
+                    loaded[i + 1].record(copy)
+            with torch.cuda.stream(compute):
+                compute.wait_event(loaded[i])
+                if timed:
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record(compute)
+                attn.launch(compute)
+                if timed:
+                    b.record(compute)
+                    marks.append((a, b))
+                attended[i].record(compute)
+            with torch.cuda.stream(copy):
+                copy.wait_event(attended[i])
+                pack(l, copy)
+        return marks
+
+    run_steps(Wm, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    marks = run_steps(K, True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    attn_ms = sorted(a.elapsed_time(b) for a, b in marks)
+    attn_ms_avg = sum(attn_ms) / len(attn_ms)
+    value = attn.flops / (ms_per_step * 1e-3) / 1e12
+
+    result = {
+        "metric": "prefill attn TFLOP/s (% MFMA peak); KV pack/unpack GB/s (% HBM peak)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"config {args.attn_config} attention "
+                               f"(P={attn.pl if len(attn.pl) < 3 else 'varlen'}, C={attn.nl if len(attn.nl) < 3 else 'varlen'}, "
+                               f"{attn.case.num_q_heads}/{attn.case.num_kv_heads} heads, D=128, 16-token pages) "
+                               f"+ one config-5 layer of KV unpack and pack (2048 pages x 32 KiB, K and V) on a second stream",
+                   "attn_flops_per_step": attn.flops, "copy_bytes_per_step": 2 * copy_bytes},
+        "pct_mfma_peak": round(100 * value / MFMA_BF16_PEAK_TFLOPS, 2),
+        "roofline": {"kernel": "attn_prefill_kernel<Bf16>", "bound": "mfma",
+                     "achieved": round(attn.flops / (attn_ms_avg * 1e-3) / 1e12, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s",
+                     "frac": round(attn.flops / (attn_ms_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "avg_launch_ms": round(attn_ms_avg, 4), "min_launch_ms": round(attn_ms[0], 4),
+                     "traffic": None},
+    }
+
+    if not args.no_extra:
+        # isolated kernels, same inputs, nothing else running
+        med, mn = attn.time_isolated()
+        result["attn_isolated"] = {"config": args.attn_config, "ms_median": round(med, 4), "ms_min": round(mn, 4),
+                                   "tflops": round(attn.flops / (med * 1e-3) / 1e12, 2),
+                                   "pct_mfma_peak": round(100 * attn.flops / (med * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2)}
+        s = torch.cuda.current_stream()
+        for name, fn in (("pack", pack), ("unpack", unpack)):
+            for l in range(LAY):
+                fn(l, s)
+            reps = 80
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(s)
+            for i in range(reps):           # 80 layers back to back, launch gaps included
+                fn(i % LAY, s)
+            b.record(s)
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / reps
+            gbs = copy_bytes / (us * 1e-6) / 1e9
+            result[f"roofline_{name}"] = {"kernel": f"kv_copy_kernel<{name}>", "bound": "hbm", "achieved": round(gbs, 1),
+                                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                                          "us_per_layer": round(us, 2), "bytes_per_launch": copy_bytes,
+                                          "traffic": None}
+        if args.attn_config != 3:
+            del attn.q, attn.k, attn.v, attn.out
+            long_ctx = Attn(3)
+            med, mn = long_ctx.time_isolated()
+            result["attn_config3"] = {"workload": "config 3: 8/1 heads, P=122880, C=8192 (128k context)",
+                                      "flops": long_ctx.flops, "ms_median": round(med, 4), "ms_min": round(mn, 4),
+                                      "tflops": round(long_ctx.flops / (med * 1e-3) / 1e12, 2),
+                                      "pct_mfma_peak": round(100 * long_ctx.flops / (med * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2)}
+
+    if args.cpu_rows > 0:
+        # the CPU oracle, as it stands, on a bounded sample of the same attention workload
+        import oracle
+        case = W.make_config_attn(args.attn_config, poison=False) if args.attn_config != attn.idx else attn.case
+        rng = np.random.default_rng(1)
+        rq = rng.integers(0, case.batch, size=args.cpu_rows)
+        rows = np.stack([rq, rng.integers(0, case.num_q_heads, size=args.cpu_rows),
+                         (rng.random(args.cpu_rows) * case.new_lens[rq]).astype(np.int64)], axis=1).astype(np.int32)
+        rows = rows[case.new_lens[rows[:, 0]] > 0]
+        row_flops = int((4 * case.head_dim * (case.prefix_lens[rows[:, 0]].astype(np.int64) + rows[:, 2] + 1)).sum())
+        t0 = time.perf_counter()
+        oracle.case_rows(case, rows)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(row_flops / dt / 1e12, 6), "unit": "TFLOP/s",
+                                  "cores": oracle.num_threads(), "kind": "oracle",
+                                  "sample": f"{rows.shape[0]} uniformly drawn (head, row) outputs of the same config-"
+                                            f"{args.attn_config} tensors, fp64, {dt:.1f} s; "
+                                            f"full tensor would take ~{case.flops() / (row_flops / dt):.0f} s"}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

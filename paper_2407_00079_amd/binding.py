@@ -45,6 +45,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2407_00079_amd.build` "
                                "(there is no CPU fallback)")
+        # torch first: its bundled HIP runtime must be the one in the process, so that the
+        # streams and device pointers it hands out belong to the runtime this library calls
+        import torch  # noqa: F401
         l = ctypes.CDLL(LIB_PATH)
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         l.mc_status_string.restype = ctypes.c_char_p

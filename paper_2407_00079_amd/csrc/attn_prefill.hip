@@ -371,6 +371,7 @@ __global__ __launch_bounds__(kThreads) void attn_prefill_kernel(const AttnArgs a
 int attn_tile_rows(int dtype) { return dtype == MC_DTYPE_BF16 ? kWaves * 1 * 32 : kWaves * 1 * 32; }
 
 hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream) {
+  (void)hipGetLastError();   // drop any stale error of earlier, unrelated runtime calls
   if (dtype == MC_DTYPE_BF16)
     attn_prefill_kernel<Bf16, 1><<<args.n_items, kThreads, 0, stream>>>(args);
   else

@@ -57,6 +57,7 @@ hipError_t launch_kv_copy(bool pack, const void* k_src, const void* v_src, void*
   const int64_t page_vecs = page_bytes / 16;
   const int slices = (int)((page_vecs + kSliceVecs - 1) / kSliceVecs);
   dim3 grid((unsigned)(n * slices), 2, 1);
+  (void)hipGetLastError();   // drop any stale error of earlier, unrelated runtime calls
   if (pack)
     kv_copy_kernel<true><<<grid, kThreads, 0, stream>>>((const u32x4*)k_src, (const u32x4*)v_src, (u32x4*)k_dst,
                                                         (u32x4*)v_dst, page_ids, page_vecs, slices);
