@@ -3,9 +3,9 @@
 // plus their own pages; the paper gives no kernel, this design is ours).
 //
 // Shape of the computation
-//   * A workgroup (4 waves) owns a tile of stacked query rows of one (request,
-//     KV head): row = token * G + head_in_group, so a K/V tile staged once in
-//     LDS feeds all G query heads that share the KV head.
+//   * A workgroup owns a tile of stacked query rows of one (request, KV head):
+//     row = token * G + head_in_group, so a K/V tile staged once in LDS feeds all
+//     G query heads that share the KV head.  Each wave takes QB blocks of 32 rows.
 //   * Scores are computed TRANSPOSED, S^T = K Q^T, on 32x32 MFMA tiles.  In the
 //     accumulator a lane then owns ONE query column (lane % 32) and 16 keys per
 //     32-key block, so the softmax row reductions are in-lane plus one exchange
@@ -14,10 +14,17 @@
 //     accumulator's row order; V^T fragments are fetched in the same order with
 //     the LDS transpose read (bf16) or plain row reads (f32).
 //   * The KV loop walks the block table 64 keys (4 pages) at a time, double
-//     buffered in LDS.  Tiles that lie wholly inside what every row of the
-//     workgroup may see run a mask-free body; only tiles that touch the chunk's
-//     diagonal compare key index against row position.
-//   * Online softmax in fp32, base 2 (scale * log2 e folded into one fma).
+//     buffered in LDS (global -> registers -> LDS, one barrier per tile).  Rows are
+//     padded in LDS so that every fragment address is lane base + constant and the
+//     reads are bank-conflict free.  Tiles that lie wholly inside what every row
+//     of the workgroup may see run a mask-free body; only tiles that touch the
+//     chunk's diagonal compare key index against row position.
+//   * Online softmax in fp32, base 2 (scale * log2 e folded into one fma).  The
+//     running maximum is only raised when a tile exceeds it by more than 2^8, so
+//     the accumulator rescale is rare; any reference below overflow gives the
+//     same quotient O / l.
+//   * Two waves per SIMD: while one wave's softmax occupies the vector ALU the
+//     other wave's MFMAs keep the matrix pipe busy.
 #include <type_traits>
 
 #include "mc_internal.h"
@@ -29,19 +36,30 @@ typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #define MC_LDS __attribute__((address_space(3)))
 
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * 64;
+#ifndef MC_WAVES
+#define MC_WAVES 8
+#endif
+#ifndef MC_QB
+#define MC_QB 1
+#endif
+#ifndef MC_SB
+#define MC_SB 1
+#endif
+
 constexpr int kTileKeys = 64;          // keys per LDS tile = 4 pages of 16
 constexpr int kPageTokens = 16;
 constexpr int kRowBytes = 256;         // one K or V row: 128 bf16 or 64 f32
 constexpr int kPageHeadBytes = kPageTokens * kRowBytes;   // 4 KiB, contiguous in the pool
-constexpr int kTileBytes = kTileKeys * kRowBytes;         // 16 KiB
-constexpr int kPagesPerTile = kTileKeys / kPageTokens;
+constexpr int kKStride = kRowBytes + 16;   // LDS row pitch of K: 16 rows x 16 B land in 64 distinct banks
+constexpr int kVStride = kRowBytes + 64;   // LDS row pitch of V: 4 rows x 64 B land in 64 distinct banks
+constexpr int kKTileBytes = kTileKeys * kKStride;
+constexpr int kVTileBytes = kTileKeys * kVStride;
+constexpr int kStageBytes = kKTileBytes + kVTileBytes;
+constexpr float kRescaleSlack = 8.0f;  // log2 units the running max may lag behind
 
 // Combine a value with the one held by lane ^ 32.  v_permlane32_swap exchanges the upper
 // half of its first register with the lower half of its second, so after it every lane
@@ -73,10 +91,6 @@ struct Bf16 {
   static constexpr int kDBlocks = kD / 32;
   typedef bf16x8 frag;
 
-  // 16-byte granule g of row `row` sits at granule g ^ swizzle(row)
-  static __device__ __forceinline__ int k_swz(int row) { return row & 15; }
-  static __device__ __forceinline__ int v_swz(int row) { return (row & 3) << 2; }
-
   static __device__ __forceinline__ f32x16 mma(frag a, frag b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
   }
@@ -84,28 +98,24 @@ struct Bf16 {
   static __device__ __forceinline__ frag load_q(const char* qrow, int kk, int half) {
     return *reinterpret_cast<const frag*>(qrow + kk * 32 + half * 16);
   }
-  // A operand: K[key][16*kk + 8*half .. +7], key = kb*32 + lane%32
-  static __device__ __forceinline__ frag load_k(const char* kt, int kb, int kk, int lane) {
-    const int row = kb * 32 + (lane & 31);
-    const int g = (kk * 2 + (lane >> 5)) ^ k_swz(row);
-    return *reinterpret_cast<const frag*>(kt + row * kRowBytes + g * 16);
+  // lane-dependent part of the K fragment address: row lane%32, column 8*half
+  static __device__ __forceinline__ int k_lane_off(int lane) { return (lane & 31) * kKStride + (lane >> 5) * 16; }
+  // A operand: K[32*kb + lane%32][16*kk + 8*half .. +7]
+  static __device__ __forceinline__ frag load_k(const char* kt_lane, int kb, int kk) {
+    return *reinterpret_cast<const frag*>(kt_lane + kb * 32 * kKStride + kk * 32);
   }
   // A operand of O^T += V^T P^T: V[key(e)][db*32 + lane%32] for the 8 keys
   // 32*kb + 16*step + 8*(e/4) + 4*half + e%4, i.e. two groups of 4 consecutive keys.
   // The transpose read returns, to lane i of a 16-lane group, element i%4 of lanes
   // i/4, 4+i/4, 8+i/4, 12+i/4: source lane s must address key s/4, columns 4*(s%4)..+3.
-  static __device__ __forceinline__ frag load_v(const char* vt, int kb, int step, int db, int lane) {
-    const int half = lane >> 5;
+  static __device__ __forceinline__ int v_lane_off(int lane) {
     const int s = lane & 15;
-    const int key0 = kb * 32 + step * 16 + half * 4 + (s >> 2);
-    const int col = db * 32 + ((lane >> 4) & 1) * 16 + (s & 3) * 4;   // element index, 8 per granule
-    const int g = col >> 3;
-    const int within = (col & 7) * 2;
-    const int off0 = key0 * kRowBytes + ((g ^ v_swz(key0)) * 16) + within;
-    const int key1 = key0 + 8;
-    const int off1 = key1 * kRowBytes + ((g ^ v_swz(key1)) * 16) + within;
-    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(vt + off0));
-    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(vt + off1));
+    return ((lane >> 5) * 4 + (s >> 2)) * kVStride + (((lane >> 4) & 1) * 16 + (s & 3) * 4) * 2;
+  }
+  static __device__ __forceinline__ frag load_v(const char* vt_lane, int kb, int step, int db) {
+    const char* p = vt_lane + (kb * 32 + step * 16) * kVStride + db * 64;
+    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(p));
+    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(p + 8 * kVStride));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
   // B operand: probabilities of accumulator registers 8*step .. 8*step+7
@@ -133,27 +143,21 @@ struct F32 {
   static constexpr int kDBlocks = kD / 32;
   typedef float frag;
 
-  static __device__ __forceinline__ int k_swz(int row) { return row & 15; }
-  static __device__ __forceinline__ int v_swz(int row) { return (row >> 2) & 1 ? 8 : 0; }
-
   static __device__ __forceinline__ f32x16 mma(frag a, frag b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
   }
   static __device__ __forceinline__ frag load_q(const char* qrow, int kk, int half) {
     return *reinterpret_cast<const float*>(qrow + (kk * 2 + half) * 4);
   }
-  static __device__ __forceinline__ frag load_k(const char* kt, int kb, int kk, int lane) {
-    const int row = kb * 32 + (lane & 31);
-    const int col = kk * 2 + (lane >> 5);
-    const int g = (col >> 2) ^ k_swz(row);
-    return *reinterpret_cast<const float*>(kt + row * kRowBytes + g * 16 + (col & 3) * 4);
+  static __device__ __forceinline__ int k_lane_off(int lane) { return (lane & 31) * kKStride + (lane >> 5) * 4; }
+  // A operand: K[32*kb + lane%32][2*kk + half]
+  static __device__ __forceinline__ frag load_k(const char* kt_lane, int kb, int kk) {
+    return *reinterpret_cast<const float*>(kt_lane + kb * 32 * kKStride + kk * 8);
   }
   // step = accumulator register r: key 32*kb + 8*(r/4) + 4*half + r%4, column db*32 + lane%32
-  static __device__ __forceinline__ frag load_v(const char* vt, int kb, int step, int db, int lane) {
-    const int key = kb * 32 + (step >> 2) * 8 + (lane >> 5) * 4 + (step & 3);
-    const int col = db * 32 + (lane & 31);
-    const int g = (col >> 2) ^ v_swz(key);
-    return *reinterpret_cast<const float*>(vt + key * kRowBytes + g * 16 + (col & 3) * 4);
+  static __device__ __forceinline__ int v_lane_off(int lane) { return (lane >> 5) * 4 * kVStride + (lane & 31) * 4; }
+  static __device__ __forceinline__ frag load_v(const char* vt_lane, int kb, int step, int db) {
+    return *reinterpret_cast<const float*>(vt_lane + (kb * 32 + (step >> 2) * 8 + (step & 3)) * kVStride + db * 128);
   }
   static __device__ __forceinline__ frag make_p(const f32x16& p, int step) { return p[step]; }
   static __device__ __forceinline__ void store4(char* orow, int col, float a, float b, float c, float d) {
@@ -165,10 +169,14 @@ struct F32 {
 // ---------------------------------------------------------------------------
 // kernel
 // ---------------------------------------------------------------------------
-template <class T, int QB>
-__global__ __launch_bounds__(kThreads) void attn_prefill_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) char smem[4 * kTileBytes];   // K0 V0 K1 V1
-  constexpr int kTileRows = kWaves * QB * 32;
+template <class T, int WAVES, int QB>
+__global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) char smem[2 * kStageBytes];   // K0 V0 K1 V1
+  constexpr int kThreads = WAVES * 64;
+  constexpr int kTileRows = WAVES * QB * 32;
+  constexpr int kGranules = kTileKeys * (kRowBytes / 16);     // 16-byte pieces of a K (or V) tile
+  constexpr int kFetch = kGranules / kThreads;                // pieces per thread, per K and per V
+  static_assert(kGranules % kThreads == 0, "tile must split evenly over the threads");
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -211,34 +219,37 @@ __global__ __launch_bounds__(kThreads) void attn_prefill_kernel(const AttnArgs a
   int n_free = (P + tok_first + 1) / kTileKeys;              // every key of these tiles is visible to every row
   n_free = n_free < n_tiles ? n_free : n_tiles;
 
-  // ---- global -> register -> LDS staging: thread copies 16 bytes of each of the tile's 4 pages
-  const char* kbase = reinterpret_cast<const char*>(a.k_pool) + (int64_t)item.kv_head * kPageHeadBytes + tid * 16;
-  const char* vbase = reinterpret_cast<const char*>(a.v_pool) + (int64_t)item.kv_head * kPageHeadBytes + tid * 16;
+  // ---- global -> register -> LDS staging.  Piece i of a thread is 16-byte granule
+  //      tid + i * kThreads of the tile: page (granule / 256), byte (granule % 256) * 16 of the page
+  const char* kbase = reinterpret_cast<const char*>(a.k_pool) + (int64_t)item.kv_head * kPageHeadBytes;
+  const char* vbase = reinterpret_cast<const char*>(a.v_pool) + (int64_t)item.kv_head * kPageHeadBytes;
   const int64_t page_stride = (int64_t)a.Hkv * kPageHeadBytes;
-  u32x4 kreg[kPagesPerTile], vreg[kPagesPerTile];
+  u32x4 kreg[kFetch], vreg[kFetch];
 
   auto fetch = [&](int tile) {
 #pragma unroll
-    for (int p = 0; p < kPagesPerTile; ++p) {
-      int lp = tile * kPagesPerTile + p;
+    for (int i = 0; i < kFetch; ++i) {
+      const int gran = tid + i * kThreads;
+      int lp = tile * (kTileKeys / kPageTokens) + (gran >> 8);
       lp = lp < last_page ? lp : last_page;                  // never index the table past the request's pages
-      const int64_t off = (int64_t)bt[lp] * page_stride;
-      kreg[p] = *reinterpret_cast<const u32x4*>(kbase + off);
-      vreg[p] = *reinterpret_cast<const u32x4*>(vbase + off);
+      const int64_t off = (int64_t)bt[lp] * page_stride + (gran & 255) * 16;
+      kreg[i] = *reinterpret_cast<const u32x4*>(kbase + off);
+      vreg[i] = *reinterpret_cast<const u32x4*>(vbase + off);
     }
   };
   auto stage = [&](int tile, int buf) {
-    char* kt = smem + buf * 2 * kTileBytes;
-    char* vt = kt + kTileBytes;
+    char* kt = smem + buf * kStageBytes;
+    char* vt = kt + kKTileBytes;
 #pragma unroll
-    for (int p = 0; p < kPagesPerTile; ++p) {
-      const int row = p * kPageTokens + (tid >> 4);
-      const int g = tid & 15;
+    for (int i = 0; i < kFetch; ++i) {
+      const int gran = tid + i * kThreads;
+      const int row = gran >> 4;
+      const int g = gran & 15;
       // slots at or past the request's length may hold anything: store zeros instead
       const bool in_seq = tile * kTileKeys + row < L;
       const u32x4 zero = {0, 0, 0, 0};
-      *reinterpret_cast<u32x4*>(kt + row * kRowBytes + ((g ^ T::k_swz(row)) * 16)) = in_seq ? kreg[p] : zero;
-      *reinterpret_cast<u32x4*>(vt + row * kRowBytes + ((g ^ T::v_swz(row)) * 16)) = in_seq ? vreg[p] : zero;
+      *reinterpret_cast<u32x4*>(kt + row * kKStride + g * 16) = in_seq ? kreg[i] : zero;
+      *reinterpret_cast<u32x4*>(vt + row * kVStride + g * 16) = in_seq ? vreg[i] : zero;
     }
   };
 
@@ -255,11 +266,13 @@ __global__ __launch_bounds__(kThreads) void attn_prefill_kernel(const AttnArgs a
       for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
   }
   const float c = a.scale_log2e;
+  const int k_lane = T::k_lane_off(lane);
+  const int v_lane = T::v_lane_off(lane);
 
   auto compute = [&](int tile, int buf, auto masked_tag) {
     constexpr bool kMasked = decltype(masked_tag)::value;
-    const char* kt = smem + buf * 2 * kTileBytes;
-    const char* vt = kt + kTileBytes;
+    const char* kt = smem + buf * kStageBytes + k_lane;
+    const char* vt = smem + buf * kStageBytes + kKTileBytes + v_lane;
     // S^T = K Q^T
     f32x16 s[QB][2];
 #pragma unroll
@@ -269,13 +282,20 @@ __global__ __launch_bounds__(kThreads) void attn_prefill_kernel(const AttnArgs a
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[qb][kb][r] = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < 2; ++kb) {
+#if MC_SB & 1
+      __builtin_amdgcn_sched_barrier(0);
+#endif
 #pragma unroll
       for (int kk = 0; kk < T::kQKSteps; ++kk) {
-        const typename T::frag kf = T::load_k(kt, kb, kk, lane);
+        const typename T::frag kf = T::load_k(kt, kb, kk);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) s[qb][kb] = T::mma(kf, qf[qb][kk], s[qb][kb]);
       }
+    }
+#if MC_SB & 2
+    __builtin_amdgcn_sched_barrier(0);
+#endif
     // online softmax per query column
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -293,37 +313,45 @@ __global__ __launch_bounds__(kThreads) void attn_prefill_kernel(const AttnArgs a
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[qb][kb][r]);
-      mx = max_with_other_half(mx);
-      const float m_new = fmaxf(m_run[qb], mx * c);
-      const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+      mx = max_with_other_half(mx) * c;
+      // raise the reference only when some column of the wave outgrew it by the slack
+      // (always true on the first tile: the reference starts at -inf)
+      if (__builtin_amdgcn_ballot_w64(mx > m_run[qb] + kRescaleSlack) != 0) {
+        const float m_new = fmaxf(m_run[qb], mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+        l_run[qb] *= alpha;
+        m_run[qb] = m_new;
+#pragma unroll
+        for (int db = 0; db < T::kDBlocks; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
+      }
+      const float m_ref = m_run[qb];
       float sum = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kb][r], c, -m_new));
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kb][r], c, -m_ref));
           s[qb][kb][r] = p;
           sum += p;
         }
-      sum = sum_with_other_half(sum);
-      l_run[qb] = l_run[qb] * alpha + sum;
-      m_run[qb] = m_new;
-#pragma unroll
-      for (int db = 0; db < T::kDBlocks; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
+      l_run[qb] += sum_with_other_half(sum);
     }
     // O^T += V^T P^T
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int st = 0; st < T::kPVSteps; ++st) {
+#if MC_SB & 4
+        __builtin_amdgcn_sched_barrier(0);
+#endif
         typename T::frag pf[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) pf[qb] = T::make_p(s[qb][kb], st);
 #pragma unroll
         for (int db = 0; db < T::kDBlocks; ++db) {
-          const typename T::frag vf = T::load_v(vt, kb, st, db, lane);
+          const typename T::frag vf = T::load_v(vt, kb, st, db);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) o[qb][db] = T::mma(vf, pf[qb], o[qb][db]);
         }
@@ -368,14 +396,14 @@ __global__ __launch_bounds__(kThreads) void attn_prefill_kernel(const AttnArgs a
 
 }  // namespace
 
-int attn_tile_rows(int dtype) { return dtype == MC_DTYPE_BF16 ? kWaves * 1 * 32 : kWaves * 1 * 32; }
+int attn_tile_rows(int dtype) { return dtype == MC_DTYPE_BF16 ? MC_WAVES * MC_QB * 32 : MC_WAVES * 32; }
 
 hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream) {
   (void)hipGetLastError();   // drop any stale error of earlier, unrelated runtime calls
   if (dtype == MC_DTYPE_BF16)
-    attn_prefill_kernel<Bf16, 1><<<args.n_items, kThreads, 0, stream>>>(args);
+    attn_prefill_kernel<Bf16, MC_WAVES, MC_QB><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
   else
-    attn_prefill_kernel<F32, 1><<<args.n_items, kThreads, 0, stream>>>(args);
+    attn_prefill_kernel<F32, MC_WAVES, 1><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
   return hipGetLastError();
 }
 
