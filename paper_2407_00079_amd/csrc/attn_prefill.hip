@@ -171,7 +171,7 @@ struct F32 {
 // ---------------------------------------------------------------------------
 template <class T, int WAVES, int QB>
 __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) char smem[2 * kStageBytes];   // K0 V0 K1 V1
+  __shared__ __attribute__((aligned(16))) char smem[3 * kStageBytes];   // three (K, V) tiles
   constexpr int kThreads = WAVES * 64;
   constexpr int kTileRows = WAVES * QB * 32;
   constexpr int kGranules = kTileKeys * (kRowBytes / 16);     // 16-byte pieces of a K (or V) tile
@@ -189,7 +189,6 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   const int P = rq.prefix;
   const int L = rq.prefix + rq.chunk;
   const int n_rows = rq.chunk * G;
-  const int32_t* __restrict__ bt = a.block_tables + (int64_t)item.req * a.max_pages;
   const int last_page = rq.pages - 1;
 
   // ---- this lane's query rows: Q fragments stay in registers for the whole KV loop
@@ -220,21 +219,35 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   n_free = n_free < n_tiles ? n_free : n_tiles;
 
   // ---- global -> register -> LDS staging.  Piece i of a thread is 16-byte granule
-  //      tid + i * kThreads of the tile: page (granule / 256), byte (granule % 256) * 16 of the page
+  //      tid + i * kThreads of the tile: page (granule / 256), byte (granule % 256) * 16 of the page.
+  //      A wave's 64 pieces of one step lie in ONE page, so the page id is a scalar load and the
+  //      page base is scalar arithmetic; the vector part of the address is a constant per thread.
   const char* kbase = reinterpret_cast<const char*>(a.k_pool) + (int64_t)item.kv_head * kPageHeadBytes;
   const char* vbase = reinterpret_cast<const char*>(a.v_pool) + (int64_t)item.kv_head * kPageHeadBytes;
   const int64_t page_stride = (int64_t)a.Hkv * kPageHeadBytes;
+  const int wave_page = __builtin_amdgcn_readfirstlane(tid >> 8);   // which page of a step this wave reads
+  const uint32_t lane_byte = (uint32_t)(tid & 255) * 16;
   u32x4 kreg[kFetch], vreg[kFetch];
+  // The block table is read through the scalar cache (it is constant while the kernel runs),
+  // one tile AHEAD of the K/V loads that need it, so no wave ever waits for a page id.
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+  const_i32_ptr btc = (const_i32_ptr)(a.block_tables + (int64_t)item.req * a.max_pages);
+  int pid[kFetch];
 
-  auto fetch = [&](int tile) {
+  auto load_ids = [&](int tile) {
 #pragma unroll
     for (int i = 0; i < kFetch; ++i) {
-      const int gran = tid + i * kThreads;
-      int lp = tile * (kTileKeys / kPageTokens) + (gran >> 8);
+      int lp = tile * (kTileKeys / kPageTokens) + i * (kThreads / 256) + wave_page;
       lp = lp < last_page ? lp : last_page;                  // never index the table past the request's pages
-      const int64_t off = (int64_t)bt[lp] * page_stride + (gran & 255) * 16;
-      kreg[i] = *reinterpret_cast<const u32x4*>(kbase + off);
-      vreg[i] = *reinterpret_cast<const u32x4*>(vbase + off);
+      pid[i] = btc[lp];
+    }
+  };
+  auto fetch = [&]() {
+#pragma unroll
+    for (int i = 0; i < kFetch; ++i) {
+      const int64_t off = (int64_t)pid[i] * page_stride;
+      kreg[i] = *reinterpret_cast<const u32x4*>(kbase + off + lane_byte);
+      vreg[i] = *reinterpret_cast<const u32x4*>(vbase + off + lane_byte);
     }
   };
   auto stage = [&](int tile, int buf) {
@@ -255,11 +268,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
 
   // ---- running softmax state and output accumulators (O^T: registers index head_dim)
   f32x16 o[QB][T::kDBlocks];
-  float m_run[QB], l_run[QB];
+  float m_run[QB], l_run[QB], l_sum[QB];   // l_sum: this lane's share of the row sum (halves merged at the end)
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     m_run[qb] = -INFINITY;
-    l_run[qb] = 0.f;
+    l_sum[qb] = 0.f;
 #pragma unroll
     for (int db = 0; db < T::kDBlocks; ++db)
 #pragma unroll
@@ -269,110 +282,148 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   const int k_lane = T::k_lane_off(lane);
   const int v_lane = T::v_lane_off(lane);
 
-  auto compute = [&](int tile, int buf, auto masked_tag) {
-    constexpr bool kMasked = decltype(masked_tag)::value;
+  // ---- the three stages of one 32-key block
+  // S^T block = K Q^T for keys [32*kb, 32*kb+32) of the tile in LDS buffer `buf`
+  auto qk_block = [&](int buf, int kb, f32x16 (&s)[QB]) {
     const char* kt = smem + buf * kStageBytes + k_lane;
-    const char* vt = smem + buf * kStageBytes + kKTileBytes + v_lane;
-    // S^T = K Q^T
-    f32x16 s[QB][2];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int r = 0; r < 16; ++r) s[qb][r] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[qb][kb][r] = 0.f;
+    for (int kk = 0; kk < T::kQKSteps; ++kk) {
+      const typename T::frag kf = T::load_k(kt, kb, kk);
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#if MC_SB & 1
-      __builtin_amdgcn_sched_barrier(0);
-#endif
-#pragma unroll
-      for (int kk = 0; kk < T::kQKSteps; ++kk) {
-        const typename T::frag kf = T::load_k(kt, kb, kk);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) s[qb][kb] = T::mma(kf, qf[qb][kk], s[qb][kb]);
-      }
+      for (int qb = 0; qb < QB; ++qb) s[qb] = T::mma(kf, qf[qb][kk], s[qb]);
     }
-#if MC_SB & 2
-    __builtin_amdgcn_sched_barrier(0);
-#endif
-    // online softmax per query column
+  };
+  // Softmax of one block is split in two so that neither part needs a branch next to MFMAs:
+  // (1) as soon as a block's scores exist: mask them if the block reaches the diagonal, take the
+  //     column maxima and raise the reference m_run if some column outgrew it by the slack
+  //     (rare, wave-uniform branch; always taken for the first block, m_run starts at -inf);
+  auto settle_reference = [&](f32x16 (&s)[QB], int key0, auto masked_tag) {
+    constexpr bool kMasked = decltype(masked_tag)::value;
+    float mx[QB];
+    bool grow = false;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       if (kMasked) {
-        // key of register r in block kb: tile*64 + kb*32 + 8*(r/4) + 4*half + r%4; visible iff <= P + tok
-        const int lim = P + tok[qb] - tile * kTileKeys - half * 4;
+        // key of register r: key0 + 8*(r/4) + 4*half + r%4; visible iff <= P + tok
+        const int lim = P + tok[qb] - key0 - half * 4;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            s[qb][kb][r] = (kb * 32 + (r >> 2) * 8 + (r & 3) <= lim) ? s[qb][kb][r] : -INFINITY;
+        for (int r = 0; r < 16; ++r) s[qb][r] = ((r >> 2) * 8 + (r & 3) <= lim) ? s[qb][r] : -INFINITY;
       }
-      float mx = s[qb][0][0];
+      mx[qb] = s[qb][0];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int r = 1; r < 16; ++r) mx[qb] = fmaxf(mx[qb], s[qb][r]);
+      mx[qb] = max_with_other_half(mx[qb]) * c;
+      grow = grow || (mx[qb] > m_run[qb] + kRescaleSlack);
+    }
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[qb][kb][r]);
-      mx = max_with_other_half(mx) * c;
-      // raise the reference only when some column of the wave outgrew it by the slack
-      // (always true on the first tile: the reference starts at -inf)
-      if (__builtin_amdgcn_ballot_w64(mx > m_run[qb] + kRescaleSlack) != 0) {
-        const float m_new = fmaxf(m_run[qb], mx);
+      for (int qb = 0; qb < QB; ++qb) {
+        const float m_new = fmaxf(m_run[qb], mx[qb]);
         const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
-        l_run[qb] *= alpha;
+        l_sum[qb] *= alpha;
         m_run[qb] = m_new;
 #pragma unroll
         for (int db = 0; db < T::kDBlocks; ++db)
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
       }
+    }
+  };
+  // (2) scores -> probabilities relative to the settled reference, in place; straight-line code
+  auto probabilities = [&](f32x16 (&s)[QB]) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
       const float m_ref = m_run[qb];
       float sum = 0.f;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][kb][r], c, -m_ref));
-          s[qb][kb][r] = p;
-          sum += p;
-        }
-      l_run[qb] += sum_with_other_half(sum);
-    }
-    // O^T += V^T P^T
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int st = 0; st < T::kPVSteps; ++st) {
-#if MC_SB & 4
-        __builtin_amdgcn_sched_barrier(0);
-#endif
-        typename T::frag pf[QB];
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) pf[qb] = T::make_p(s[qb][kb], st);
-#pragma unroll
-        for (int db = 0; db < T::kDBlocks; ++db) {
-          const typename T::frag vf = T::load_v(vt, kb, st, db);
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb) o[qb][db] = T::mma(vf, pf[qb], o[qb][db]);
-        }
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][r], c, -m_ref));
+        s[qb][r] = p;
+        sum += p;
       }
+      l_sum[qb] += sum;
+    }
+  };
+  // O^T += V^T P^T for the block's 32 keys
+  auto pv_block = [&](int buf, int kb, const f32x16 (&s)[QB]) {
+    const char* vt = smem + buf * kStageBytes + kKTileBytes + v_lane;
+#pragma unroll
+    for (int st = 0; st < T::kPVSteps; ++st) {
+      typename T::frag pf[QB];
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) pf[qb] = T::make_p(s[qb], st);
+#pragma unroll
+      for (int db = 0; db < T::kDBlocks; ++db) {
+        const typename T::frag vf = T::load_v(vt, kb, st, db);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) o[qb][db] = T::mma(vf, pf[qb], o[qb][db]);
+      }
+    }
   };
 
-  // ---- KV loop, double buffered
-  fetch(0);
+  // ---- KV loop.  Software pipeline over 32-key blocks: one step turns the settled scores of
+  //      block j into probabilities and accumulates P V, while the score MFMAs of block j+1 are
+  //      in the same straight-line region, so the matrix pipe works under the vector ALU.
+  //      Tiles are triple buffered in LDS: tile t+1 is staged in the middle of tile t (one
+  //      barrier per tile), and its buffer was last read two tiles ago.
+  f32x16 s_cur[QB], s_next[QB];
+  auto step = [&](int buf_cur, int kb_cur, int buf_nxt, int kb_nxt, int key0_nxt, auto mask_next_tag) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) s_cur[qb] = s_next[qb];
+    qk_block(buf_nxt, kb_nxt, s_next);
+    probabilities(s_cur);
+    pv_block(buf_cur, kb_cur, s_cur);
+    settle_reference(s_next, key0_nxt, mask_next_tag);
+  };
+
+  load_ids(0);
+  fetch();
+  load_ids(1);
+  // every load issued so far (Q fragments included) has landed before the loop starts, so the
+  // loop body never waits on the vector-memory counter for anything but its own prefetch
+  __builtin_amdgcn_s_waitcnt(0);
   stage(0, 0);
-  __syncthreads();
-  for (int tile = 0; tile < n_tiles; ++tile) {
-    const int buf = tile & 1;
-    const bool more = tile + 1 < n_tiles;
-    if (more) fetch(tile + 1);
-    if (tile < n_free)
-      compute(tile, buf, std::false_type{});
-    else
-      compute(tile, buf, std::true_type{});
-    if (more) stage(tile + 1, buf ^ 1);
-    __syncthreads();
+  if (n_tiles > 1) {
+    fetch();
+    load_ids(2);
   }
+  __syncthreads();
+  qk_block(0, 0, s_next);
+  settle_reference(s_next, 0, std::true_type{});
+  int buf = 0;
+  // one tile = two steps with the staging of the next tile and the barrier between them;
+  // mask_tag says whether the blocks SETTLED in this tile (its second block and the first
+  // block of the next tile) may reach the diagonal
+  auto tile_body = [&](int tile, bool more, auto mask_tag) {
+    const int buf_next = buf == 2 ? 0 : buf + 1;
+    step(buf, 0, buf, 1, tile * kTileKeys + 32, mask_tag);
+    if (more) {
+      stage(tile + 1, buf_next);
+      if (tile + 2 < n_tiles) {
+        fetch();               // K/V of tile + 2, through the ids loaded one tile ago
+        load_ids(tile + 3);
+      }
+    }
+    __syncthreads();
+    if (more) {
+      step(buf, 1, buf_next, 0, (tile + 1) * kTileKeys, mask_tag);
+    } else {
+      probabilities(s_next);
+      pv_block(buf, 1, s_next);
+    }
+    buf = buf_next;
+  };
+  int tile = 0;
+  // tiles whose own second block and whose successor's first block are fully visible
+  for (; tile < n_free - 1; ++tile) tile_body(tile, true, std::false_type{});
+  // the rest (the tiles on the chunk's diagonal, and one tile before them)
+  for (; tile < n_tiles; ++tile) tile_body(tile, tile + 1 < n_tiles, std::true_type{});
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) l_run[qb] = sum_with_other_half(l_sum[qb]);
 
   // ---- epilogue: normalise, round, store; lane holds 4 consecutive columns per (db, r/4)
 #pragma unroll
