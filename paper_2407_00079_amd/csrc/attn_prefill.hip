@@ -46,8 +46,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef MC_QB
 #define MC_QB 1
 #endif
-#ifndef MC_SB
-#define MC_SB 1
+#ifndef MC_FENCE
+#define MC_FENCE 0
 #endif
 
 constexpr int kTileKeys = 64;          // keys per LDS tile = 4 pages of 16
@@ -234,7 +234,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   const_i32_ptr btc = (const_i32_ptr)(a.block_tables + (int64_t)item.req * a.max_pages);
   int pid[kFetch];
 
-  auto load_ids = [&](int tile) {
+  auto load_ids = [&](int tile) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < kFetch; ++i) {
       int lp = tile * (kTileKeys / kPageTokens) + i * (kThreads / 256) + wave_page;
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
       pid[i] = btc[lp];
     }
   };
-  auto fetch = [&]() {
+  auto fetch = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < kFetch; ++i) {
       const int64_t off = (int64_t)pid[i] * page_stride;
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
       vreg[i] = *reinterpret_cast<const u32x4*>(vbase + off + lane_byte);
     }
   };
-  auto stage = [&](int tile, int buf) {
+  auto stage = [&](int tile, int buf) __attribute__((always_inline)) {
     char* kt = smem + buf * kStageBytes;
     char* vt = kt + kKTileBytes;
 #pragma unroll
@@ -371,12 +371,21 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   //      Tiles are triple buffered in LDS: tile t+1 is staged in the middle of tile t (one
   //      barrier per tile), and its buffer was last read two tiles ago.
   f32x16 s_cur[QB], s_next[QB];
-  auto step = [&](int buf_cur, int kb_cur, int buf_nxt, int kb_nxt, int key0_nxt, auto mask_next_tag) {
+  auto step = [&](int buf_cur, int kb_cur, int buf_nxt, int kb_nxt, int key0_nxt, auto mask_next_tag) __attribute__((always_inline)) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) s_cur[qb] = s_next[qb];
+#if MC_FENCE & 1
+    __builtin_amdgcn_sched_barrier(0);
+#endif
     qk_block(buf_nxt, kb_nxt, s_next);
     probabilities(s_cur);
+#if MC_FENCE & 2
+    __builtin_amdgcn_sched_barrier(0);
+#endif
     pv_block(buf_cur, kb_cur, s_cur);
+#if MC_FENCE & 4
+    __builtin_amdgcn_sched_barrier(0);
+#endif
     settle_reference(s_next, key0_nxt, mask_next_tag);
   };
 
@@ -398,7 +407,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   // one tile = two steps with the staging of the next tile and the barrier between them;
   // mask_tag says whether the blocks SETTLED in this tile (its second block and the first
   // block of the next tile) may reach the diagonal
-  auto tile_body = [&](int tile, bool more, auto mask_tag) {
+  auto tile_body = [&](int tile, bool more, auto mask_tag) __attribute__((always_inline)) {
     const int buf_next = buf == 2 ? 0 : buf + 1;
     step(buf, 0, buf, 1, tile * kTileKeys + 32, mask_tag);
     if (more) {
