@@ -26,15 +26,29 @@ MFMA_BF16_PEAK_TFLOPS = 2516.6   # 256 CU x 4 SIMD x 1024 flop/cycle x 2.4 GHz
 HBM_PEAK_GBS = 8000.0
 
 
+def measured_traffic():
+    """HBM bytes per launch from the committed rocprofv3 counter summary (None if it is absent)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_bench_step.txt")
+    out = {}
+    try:
+        for line in open(path):
+            if "=" in line and not line.startswith("#"):
+                k, v = line.split("=")
+                out[k.strip()] = int(v)
+    except OSError:
+        pass
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--attn-config", type=int, default=2, choices=(2, 3, 4),
                     help="attention workload of the step (default: configuration 2)")
     ap.add_argument("--layers", type=int, default=8, help="distinct per-layer pools the steps cycle through")
-    ap.add_argument("--cpu-rows", type=int, default=12288, help="rows the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-rows", type=int, default=65536, help="rows the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-extra", action="store_true", help="skip the isolated / configuration-3 measurements")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -152,6 +166,12 @@ def main():
     attn_ms = sorted(a.elapsed_time(b) for a, b in marks)
     attn_ms_avg = sum(attn_ms) / len(attn_ms)
     value = attn.flops / (ms_per_step * 1e-3) / 1e12
+    traffic = measured_traffic()
+
+    def hbm(prefix):
+        r, w = traffic.get(prefix + "_read_bytes"), traffic.get(prefix + "_write_bytes")
+        return None if r is None or w is None else {"read_bytes": r, "write_bytes": w, "unit": "B per launch",
+                                                    "source": "profiles/hbm_traffic_bench_step.txt"}
 
     result = {
         "metric": "prefill attn TFLOP/s (% MFMA peak); KV pack/unpack GB/s (% HBM peak)",
@@ -169,7 +189,8 @@ def main():
                      "unit": "TFLOP/s",
                      "frac": round(attn.flops / (attn_ms_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                      "avg_launch_ms": round(attn_ms_avg, 4), "min_launch_ms": round(attn_ms[0], 4),
-                     "traffic": None},
+                     "launch_ms": [round(a.elapsed_time(b), 3) for a, b in marks],
+                     "traffic": hbm("attn_config2") if args.attn_config == 2 else None},
     }
 
     if not args.no_extra:
@@ -194,7 +215,7 @@ def main():
             result[f"roofline_{name}"] = {"kernel": f"kv_copy_kernel<{name}>", "bound": "hbm", "achieved": round(gbs, 1),
                                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                                           "us_per_layer": round(us, 2), "bytes_per_launch": copy_bytes,
-                                          "traffic": None}
+                                          "traffic": hbm(name)}
         if args.attn_config != 3:
             del attn.q, attn.k, attn.v, attn.out
             long_ctx = Attn(3)

@@ -33,9 +33,11 @@ size_t max_items(const mc_attn_params* p, int32_t batch, int64_t total_new_token
 }
 
 // Pinned host slots the work list is written to before its asynchronous upload.  A slot is
-// reused only after the event recorded behind its last upload has completed, so calls never
-// wait for the stream's earlier work and the host copy outlives the transfer.  Host memory
-// only; grows to the largest work list seen and is kept until the process ends.
+// reused only after the event recorded behind its last upload has completed, so the host copy
+// outlives the transfer.  A call never waits for the stream's earlier work: if every slot is
+// still in flight a new one is added (up to kMaxSlots; only then does a call block on the
+// oldest).  Host memory only, 64 KiB or the largest work list seen per slot, kept until the
+// process ends.
 class StagingRing {
  public:
   // returns a slot with at least `bytes` of pinned memory, or nullptr if HIP refuses
@@ -43,19 +45,31 @@ class StagingRing {
     std::lock_guard<std::mutex> lock(mu_);
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return nullptr;
-    Slot& s = slots_[next_];
-    if (s.ev != nullptr && s.dev == dev) {
-      if (s.busy && hipEventSynchronize(s.ev) != hipSuccess) return nullptr;
-    } else {
-      // first use, or the slot belongs to another device: rebuild it for this one
-      if (s.ev != nullptr) {
-        (void)hipEventSynchronize(s.ev);
-        (void)hipEventDestroy(s.ev);
-        s.ev = nullptr;
-      }
+    int pick = -1;
+    const int n = (int)slots_.size();
+    for (int k = 0; k < n && pick < 0; ++k) {
+      const int i = (next_ + k) % n;
+      Slot& s = slots_[i];
+      if (s.dev != dev) continue;
+      if (!s.busy || hipEventQuery(s.ev) == hipSuccess) pick = i;
+    }
+    if (pick < 0 && n < kMaxSlots) {
+      Slot s;
       if (hipEventCreateWithFlags(&s.ev, hipEventDisableTiming) != hipSuccess) return nullptr;
       s.dev = dev;
+      slots_.push_back(s);
+      pick = n;
     }
+    if (pick < 0) {
+      // everything in flight and the ring is full: wait for the oldest slot of this device
+      for (int k = 0; k < n && pick < 0; ++k) {
+        const int i = (next_ + k) % n;
+        if (slots_[i].dev == dev) pick = i;
+      }
+      if (pick < 0) return nullptr;   // ring full of other devices' slots
+      if (hipEventSynchronize(slots_[pick].ev) != hipSuccess) return nullptr;
+    }
+    Slot& s = slots_[pick];
     s.busy = false;
     if (s.cap < bytes) {
       if (s.host != nullptr) (void)hipHostFree(s.host);
@@ -65,8 +79,8 @@ class StagingRing {
       if (hipHostMalloc(&s.host, want, hipHostMallocDefault) != hipSuccess) return nullptr;
       s.cap = want;
     }
-    *slot_out = next_;
-    next_ = (next_ + 1) % kSlots;
+    *slot_out = pick;
+    next_ = (pick + 1) % (int)slots_.size();
     return s.host;
   }
   bool release_after(int slot, hipStream_t stream) {
@@ -78,7 +92,7 @@ class StagingRing {
   }
 
  private:
-  static constexpr int kSlots = 8;
+  static constexpr int kMaxSlots = 256;
   struct Slot {
     void* host = nullptr;
     size_t cap = 0;
@@ -87,7 +101,7 @@ class StagingRing {
     bool busy = false;
   };
   std::mutex mu_;
-  Slot slots_[kSlots];
+  std::vector<Slot> slots_;
   int next_ = 0;
 };
 
@@ -233,7 +247,7 @@ static mc_status check_copy(const void* a, const void* b, int64_t num_pages, int
   if (num_pages == 0) return MC_ERR_SHAPE;
   if (!aligned16(a) || !aligned16(b) || !aligned16(c) || !aligned16(d) || (reinterpret_cast<uintptr_t>(ids) & 3u))
     return MC_ERR_ALIGN;
-  const int64_t slices = (page_bytes / 16 + 1023) / 1024;
+  const int64_t slices = (page_bytes / 16 + mc::kv_copy_slice_vecs() - 1) / mc::kv_copy_slice_vecs();
   if (n > INT32_MAX || n * slices > INT32_MAX) return MC_ERR_RANGE;
   return MC_OK;
 }

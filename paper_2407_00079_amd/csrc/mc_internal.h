@@ -44,6 +44,9 @@ int attn_tile_rows(int dtype);
 // enqueue the attention kernel over args.n_items work items
 hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream);
 
+// 16-byte vectors of a page one copy workgroup moves (host needs it for the grid-size range check)
+int kv_copy_slice_vecs();
+
 // enqueue gather (pack) or scatter (unpack) of n pages of page_bytes for K and V
 hipError_t launch_kv_copy(bool pack, const void* k_src, const void* v_src, void* k_dst, void* v_dst,
                           const int32_t* page_ids, int64_t n, int64_t page_bytes, hipStream_t stream);
