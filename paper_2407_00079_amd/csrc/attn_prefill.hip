@@ -13,11 +13,12 @@
 //     operand of O^T += V^T P^T.  The key order inside that contraction is the
 //     accumulator's row order; V^T fragments are fetched in the same order with
 //     the LDS transpose read (bf16) or plain row reads (f32).
-//   * The KV loop walks the block table 64 keys (4 pages) at a time, double
-//     buffered in LDS (global -> registers -> LDS, one barrier per tile).  Rows are
-//     padded in LDS so that every fragment address is lane base + constant and the
-//     reads are bank-conflict free.  Tiles that lie wholly inside what every row
-//     of the workgroup may see run a mask-free body; only tiles that touch the
+//   * The KV loop walks the block table 64 keys (4 pages) at a time.  Tiles are
+//     triple buffered in LDS and filled by direct global->LDS loads (no registers,
+//     no LDS stores; one barrier per tile).  The 16-byte granules of a row are XOR
+//     swizzled so that fragment reads are bank-conflict free; a fragment address is
+//     (lane base XOR constant) + constant.  Tiles that lie wholly inside what every
+//     row of the workgroup may see run a mask-free body; only tiles that touch the
 //     chunk's diagonal compare key index against row position.
 //   * Online softmax in fp32, base 2 (scale * log2 e folded into one fma).  The
 //     running maximum is only raised when a tile exceeds it by more than 2^8, so
@@ -49,16 +50,20 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef MC_FENCE
 #define MC_FENCE 0
 #endif
+#ifndef MC_SGB
+#define MC_SGB 0
+#endif
+#ifndef MC_KPRE
+#define MC_KPRE 2
+#endif
 
 constexpr int kTileKeys = 64;          // keys per LDS tile = 4 pages of 16
 constexpr int kPageTokens = 16;
 constexpr int kRowBytes = 256;         // one K or V row: 128 bf16 or 64 f32
 constexpr int kPageHeadBytes = kPageTokens * kRowBytes;   // 4 KiB, contiguous in the pool
-constexpr int kKStride = kRowBytes + 16;   // LDS row pitch of K: 16 rows x 16 B land in 64 distinct banks
-constexpr int kVStride = kRowBytes + 64;   // LDS row pitch of V: 4 rows x 64 B land in 64 distinct banks
-constexpr int kKTileBytes = kTileKeys * kKStride;
-constexpr int kVTileBytes = kTileKeys * kVStride;
-constexpr int kStageBytes = kKTileBytes + kVTileBytes;
+constexpr int kKTileBytes = kTileKeys * kRowBytes;        // 16 KiB; rows dense, granules swizzled
+constexpr int kVTileBytes = kTileKeys * kRowBytes;
+constexpr int kStageBytes = kKTileBytes + kVTileBytes;    // a multiple of 32 KiB: XOR constants (< 256) never touch it
 constexpr float kRescaleSlack = 8.0f;  // log2 units the running max may lag behind
 
 // Combine a value with the one held by lane ^ 32.  v_permlane32_swap exchanges the upper
@@ -98,24 +103,37 @@ struct Bf16 {
   static __device__ __forceinline__ frag load_q(const char* qrow, int kk, int half) {
     return *reinterpret_cast<const frag*>(qrow + kk * 32 + half * 16);
   }
-  // lane-dependent part of the K fragment address: row lane%32, column 8*half
-  static __device__ __forceinline__ int k_lane_off(int lane) { return (lane & 31) * kKStride + (lane >> 5) * 16; }
+  // LDS swizzle: 16-byte granule g of tile row r is stored at granule g ^ swz(r).
+  // K: 16 rows read the same logical granule at once -> spread them over all 16 positions.
+  // V: a transpose read touches 4 consecutive rows x 64 B -> rotate the 64-byte quarter by the row.
+  static __device__ __forceinline__ int k_swz(int row) { return row & 15; }
+  static __device__ __forceinline__ int v_swz(int row) { return (row & 3) << 2; }
+  // lane-dependent part of the K fragment address (row r = lane%32, granule 2*kk + half):
+  // r*256 + ((2*kk + half) ^ (r & 15)) * 16  ==  k_lane_off ^ (kk << 5)
+  static __device__ __forceinline__ int k_lane_off(int lane) {
+    const int r = lane & 31, h = lane >> 5;
+    return r * kRowBytes + (((r >> 1) & 7) << 5) + ((h ^ (r & 1)) << 4);
+  }
   // A operand: K[32*kb + lane%32][16*kk + 8*half .. +7]
-  static __device__ __forceinline__ frag load_k(const char* kt_lane, int kb, int kk) {
-    return *reinterpret_cast<const frag*>(kt_lane + kb * 32 * kKStride + kk * 32);
+  static __device__ __forceinline__ frag load_k(uint32_t kt_lane, int kb, int kk) {
+    return *reinterpret_cast<MC_LDS const frag*>((kt_lane ^ (uint32_t)(kk << 5)) + kb * 32 * kRowBytes);
   }
   // A operand of O^T += V^T P^T: V[key(e)][db*32 + lane%32] for the 8 keys
   // 32*kb + 16*step + 8*(e/4) + 4*half + e%4, i.e. two groups of 4 consecutive keys.
   // The transpose read returns, to lane i of a 16-lane group, element i%4 of lanes
   // i/4, 4+i/4, 8+i/4, 12+i/4: source lane s must address key s/4, columns 4*(s%4)..+3.
+  // With the swizzle, granule 4*db + gl of row r sits at ((db ^ (r & 3)) << 2) + gl, so the address
+  // is v_lane_off ^ (db << 6) plus a row offset that is a multiple of 4 rows.
   static __device__ __forceinline__ int v_lane_off(int lane) {
     const int s = lane & 15;
-    return ((lane >> 5) * 4 + (s >> 2)) * kVStride + (((lane >> 4) & 1) * 16 + (s & 3) * 4) * 2;
+    const int r = (lane >> 5) * 4 + (s >> 2);
+    const int col_bytes = (((lane >> 4) & 1) * 16 + (s & 3) * 4) * 2;   // < 64
+    return r * kRowBytes + ((r & 3) << 6) + col_bytes;
   }
-  static __device__ __forceinline__ frag load_v(const char* vt_lane, int kb, int step, int db) {
-    const char* p = vt_lane + (kb * 32 + step * 16) * kVStride + db * 64;
+  static __device__ __forceinline__ frag load_v(uint32_t vt_lane, int kb, int step, int db) {
+    const uint32_t p = (vt_lane ^ (uint32_t)(db << 6)) + (kb * 32 + step * 16) * kRowBytes;
     bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(p));
-    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(p + 8 * kVStride));
+    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(p + 8 * kRowBytes));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
   // B operand: probabilities of accumulator registers 8*step .. 8*step+7
@@ -124,6 +142,19 @@ struct Bf16 {
 #pragma unroll
     for (int e = 0; e < 8; ++e) f[e] = (__bf16)p[step * 8 + e];
     return f;
+  }
+  // sum of a block's 16 probabilities AS ROUNDED to bf16 (the values P V multiplies), two per
+  // v_dot2c_f32_bf16 with fp32 accumulation; the conversions are the ones make_p needs anyway
+  static __device__ __forceinline__ float block_sum(const f32x16& p) {
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    float acc = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const bf16x2 pr = {(__bf16)p[2 * e], (__bf16)p[2 * e + 1]};
+      acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
+    }
+    return acc;
   }
   // four consecutive output columns
   static __device__ __forceinline__ void store4(char* orow, int col, float a, float b, float c, float d) {
@@ -149,17 +180,32 @@ struct F32 {
   static __device__ __forceinline__ frag load_q(const char* qrow, int kk, int half) {
     return *reinterpret_cast<const float*>(qrow + (kk * 2 + half) * 4);
   }
-  static __device__ __forceinline__ int k_lane_off(int lane) { return (lane & 31) * kKStride + (lane >> 5) * 4; }
+  static __device__ __forceinline__ int k_swz(int row) { return row & 15; }
+  static __device__ __forceinline__ int v_swz(int) { return 0; }
+  // column 2*kk + half lies in granule kk/2 at byte ((kk & 1) * 2 + half) * 4:
+  // r*256 + ((kk/2) ^ (r & 15)) * 16 + ...  ==  (k_lane_off ^ ((kk/2) << 4)) + (kk & 1) * 8
+  static __device__ __forceinline__ int k_lane_off(int lane) {
+    const int r = lane & 31;
+    return r * kRowBytes + ((r & 15) << 4) + (lane >> 5) * 4;
+  }
   // A operand: K[32*kb + lane%32][2*kk + half]
-  static __device__ __forceinline__ frag load_k(const char* kt_lane, int kb, int kk) {
-    return *reinterpret_cast<const float*>(kt_lane + kb * 32 * kKStride + kk * 8);
+  static __device__ __forceinline__ frag load_k(uint32_t kt_lane, int kb, int kk) {
+    return *reinterpret_cast<MC_LDS const float*>((kt_lane ^ (uint32_t)((kk >> 1) << 4)) + (kk & 1) * 8 +
+                                                  kb * 32 * kRowBytes);
   }
   // step = accumulator register r: key 32*kb + 8*(r/4) + 4*half + r%4, column db*32 + lane%32
-  static __device__ __forceinline__ int v_lane_off(int lane) { return (lane >> 5) * 4 * kVStride + (lane & 31) * 4; }
-  static __device__ __forceinline__ frag load_v(const char* vt_lane, int kb, int step, int db) {
-    return *reinterpret_cast<const float*>(vt_lane + (kb * 32 + (step >> 2) * 8 + (step & 3)) * kVStride + db * 128);
+  static __device__ __forceinline__ int v_lane_off(int lane) { return (lane >> 5) * 4 * kRowBytes + (lane & 31) * 4; }
+  static __device__ __forceinline__ frag load_v(uint32_t vt_lane, int kb, int step, int db) {
+    return *reinterpret_cast<MC_LDS const float*>(vt_lane + (kb * 32 + (step >> 2) * 8 + (step & 3)) * kRowBytes +
+                                                  db * 128);
   }
   static __device__ __forceinline__ frag make_p(const f32x16& p, int step) { return p[step]; }
+  static __device__ __forceinline__ float block_sum(const f32x16& p) {
+    float acc = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc += p[r];
+    return acc;
+  }
   static __device__ __forceinline__ void store4(char* orow, int col, float a, float b, float c, float d) {
     f32x4 v = {a, b, c, d};
     *reinterpret_cast<f32x4*>(orow + col * 4) = v;
@@ -218,53 +264,58 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   int n_free = (P + tok_first + 1) / kTileKeys;              // every key of these tiles is visible to every row
   n_free = n_free < n_tiles ? n_free : n_tiles;
 
-  // ---- global -> register -> LDS staging.  Piece i of a thread is 16-byte granule
-  //      tid + i * kThreads of the tile: page (granule / 256), byte (granule % 256) * 16 of the page.
-  //      A wave's 64 pieces of one step lie in ONE page, so the page id is a scalar load and the
-  //      page base is scalar arithmetic; the vector part of the address is a constant per thread.
+  // ---- global -> LDS, no registers in between.  One wave instruction writes 1 KiB of LDS (lane i
+  //      its 16 bytes at +16*i): 4 tile rows x 16 granules, all inside one page.  Lane i fetches,
+  //      for LDS granule position i%16 of row i/16, the logical granule (i%16) ^ swz(row).
+  //      Chunk c = wave + i*WAVES (rows 4c..4c+3, page c/4 of the tile) is this wave's i-th piece.
   const char* kbase = reinterpret_cast<const char*>(a.k_pool) + (int64_t)item.kv_head * kPageHeadBytes;
   const char* vbase = reinterpret_cast<const char*>(a.v_pool) + (int64_t)item.kv_head * kPageHeadBytes;
   const int64_t page_stride = (int64_t)a.Hkv * kPageHeadBytes;
-  const int wave_page = __builtin_amdgcn_readfirstlane(tid >> 8);   // which page of a step this wave reads
-  const uint32_t lane_byte = (uint32_t)(tid & 255) * 16;
-  u32x4 kreg[kFetch], vreg[kFetch];
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int wave_page = wave_u >> 2;                         // page of the tile this wave's first chunk lies in
   // The block table is read through the scalar cache (it is constant while the kernel runs),
   // one tile AHEAD of the K/V loads that need it, so no wave ever waits for a page id.
   typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
   const_i32_ptr btc = (const_i32_ptr)(a.block_tables + (int64_t)item.req * a.max_pages);
+  const int64_t first_page_off = (int64_t)btc[0] * page_stride;   // page of key 0: always valid
   int pid[kFetch];
+  uint32_t k_src[kFetch], v_src[kFetch];   // byte offset inside the (page, head) block each lane copies from
+  int tile_row[kFetch];
+#pragma unroll
+  for (int i = 0; i < kFetch; ++i) {
+    const int row = (wave_u + i * WAVES) * 4 + (lane >> 4);
+    const int pg = lane & 15;
+    tile_row[i] = row;
+    k_src[i] = (uint32_t)((row & 15) * kRowBytes + ((pg ^ T::k_swz(row)) << 4));
+    v_src[i] = (uint32_t)((row & 15) * kRowBytes + ((pg ^ T::v_swz(row)) << 4));
+  }
 
   auto load_ids = [&](int tile) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < kFetch; ++i) {
-      int lp = tile * (kTileKeys / kPageTokens) + i * (kThreads / 256) + wave_page;
+      int lp = tile * (kTileKeys / kPageTokens) + i * (WAVES / 4) + wave_page;
       lp = lp < last_page ? lp : last_page;                  // never index the table past the request's pages
       pid[i] = btc[lp];
     }
   };
-  auto fetch = [&]() __attribute__((always_inline)) {
+  // enqueue the copy of tile `tile` (page ids in pid[]) into LDS buffer `buf`
+  auto fetch = [&](int tile, int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < kFetch; ++i) {
-      const int64_t off = (int64_t)pid[i] * page_stride;
-      kreg[i] = *reinterpret_cast<const u32x4*>(kbase + off + lane_byte);
-      vreg[i] = *reinterpret_cast<const u32x4*>(vbase + off + lane_byte);
+      // Slots at or past the request's length may hold anything (NaN would survive p = 0 in P V):
+      // those lanes copy row 0 of the request's first page instead; the causal mask hides the key.
+      const bool in_seq = tile * kTileKeys + tile_row[i] < L;
+      const int64_t page_off = (int64_t)pid[i] * page_stride;
+      const char* ks = kbase + (in_seq ? page_off + k_src[i] : first_page_off + (k_src[i] & 255));
+      const char* vs = vbase + (in_seq ? page_off + v_src[i] : first_page_off + (v_src[i] & 255));
+      char* dst = smem + buf * kStageBytes + (wave_u + i * WAVES) * 1024;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ks, (MC_LDS void*)dst, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)vs,
+                                       (MC_LDS void*)(dst + kKTileBytes), 16, 0, 0);
     }
   };
-  auto stage = [&](int tile, int buf) __attribute__((always_inline)) {
-    char* kt = smem + buf * kStageBytes;
-    char* vt = kt + kKTileBytes;
-#pragma unroll
-    for (int i = 0; i < kFetch; ++i) {
-      const int gran = tid + i * kThreads;
-      const int row = gran >> 4;
-      const int g = gran & 15;
-      // slots at or past the request's length may hold anything: store zeros instead
-      const bool in_seq = tile * kTileKeys + row < L;
-      const u32x4 zero = {0, 0, 0, 0};
-      *reinterpret_cast<u32x4*>(kt + row * kKStride + g * 16) = in_seq ? kreg[i] : zero;
-      *reinterpret_cast<u32x4*>(vt + row * kVStride + g * 16) = in_seq ? vreg[i] : zero;
-    }
-  };
+  // wait until this wave's copies have landed (vmcnt(0); the other counters are left alone)
+  auto copies_landed = [&]() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };
 
   // ---- running softmax state and output accumulators (O^T: registers index head_dim)
   f32x16 o[QB][T::kDBlocks];
@@ -279,13 +330,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
       for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
   }
   const float c = a.scale_log2e;
-  const int k_lane = T::k_lane_off(lane);
-  const int v_lane = T::v_lane_off(lane);
+  const uint32_t smem_base = (uint32_t)(uintptr_t)(MC_LDS char*)smem;
+  const uint32_t k_lane = smem_base + T::k_lane_off(lane);
+  const uint32_t v_lane = smem_base + kKTileBytes + T::v_lane_off(lane);
 
   // ---- the three stages of one 32-key block
   // S^T block = K Q^T for keys [32*kb, 32*kb+32) of the tile in LDS buffer `buf`
   auto qk_block = [&](int buf, int kb, f32x16 (&s)[QB]) {
-    const char* kt = smem + buf * kStageBytes + k_lane;
+    const uint32_t kt = k_lane + buf * kStageBytes;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -338,19 +390,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       const float m_ref = m_run[qb];
-      float sum = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][r], c, -m_ref));
-        s[qb][r] = p;
-        sum += p;
-      }
-      l_sum[qb] += sum;
+      for (int r = 0; r < 16; ++r) s[qb][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][r], c, -m_ref));
+      l_sum[qb] += T::block_sum(s[qb]);
     }
   };
   // O^T += V^T P^T for the block's 32 keys
   auto pv_block = [&](int buf, int kb, const f32x16 (&s)[QB]) {
-    const char* vt = smem + buf * kStageBytes + kKTileBytes + v_lane;
+    const uint32_t vt = v_lane + buf * kStageBytes;
 #pragma unroll
     for (int st = 0; st < T::kPVSteps; ++st) {
       typename T::frag pf[QB];
@@ -368,58 +415,77 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   // ---- KV loop.  Software pipeline over 32-key blocks: one step turns the settled scores of
   //      block j into probabilities and accumulates P V, while the score MFMAs of block j+1 are
   //      in the same straight-line region, so the matrix pipe works under the vector ALU.
-  //      Tiles are triple buffered in LDS: tile t+1 is staged in the middle of tile t (one
-  //      barrier per tile), and its buffer was last read two tiles ago.
+  //      Tiles are triple buffered in LDS: the copy of tile t+2 is enqueued at the start of
+  //      tile t (right after the one barrier per tile), into the buffer tile t-1 has just left.
   f32x16 s_cur[QB], s_next[QB];
-  auto step = [&](int buf_cur, int kb_cur, int buf_nxt, int kb_nxt, int key0_nxt, auto mask_next_tag) __attribute__((always_inline)) {
+  // The first kKPre K fragments of the block whose scores the NEXT step computes are fetched a
+  // step ahead; the rest are read at the start of that step, under its first MFMAs.
+  constexpr int kKPre = T::kQKSteps < MC_KPRE ? T::kQKSteps : MC_KPRE;
+  typename T::frag kf[kKPre];
+  auto load_k_block = [&](int buf, int kb) __attribute__((always_inline)) {
+    const uint32_t kt = k_lane + buf * kStageBytes;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) s_cur[qb] = s_next[qb];
-#if MC_FENCE & 1
-    __builtin_amdgcn_sched_barrier(0);
-#endif
-    qk_block(buf_nxt, kb_nxt, s_next);
+    for (int kk = 0; kk < kKPre; ++kk) kf[kk] = T::load_k(kt, kb, kk);
+  };
+  // One step: scores of block j+1 from the K fragments fetched during the previous step,
+  // probabilities and P V of block j, then the K fragments of block j+2 (their LDS latency
+  // is covered by a whole step), then the reference check for block j+1.
+  auto step = [&](int buf_cur, int kb_cur, int buf_nxt, int kb_nxt, int key0_nxt, int buf_pre, int kb_pre,
+                  auto mask_next_tag) __attribute__((always_inline)) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      s_cur[qb] = s_next[qb];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_next[qb][r] = 0.f;
+    }
+    {
+      const uint32_t kt = k_lane + buf_nxt * kStageBytes;
+#pragma unroll
+      for (int kk = 0; kk < T::kQKSteps; ++kk) {
+        const typename T::frag k_now = kk < kKPre ? kf[kk < kKPre ? kk : 0] : T::load_k(kt, kb_nxt, kk);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) s_next[qb] = T::mma(k_now, qf[qb][kk], s_next[qb]);
+      }
+    }
+    load_k_block(buf_pre, kb_pre);
     probabilities(s_cur);
-#if MC_FENCE & 2
-    __builtin_amdgcn_sched_barrier(0);
-#endif
     pv_block(buf_cur, kb_cur, s_cur);
-#if MC_FENCE & 4
-    __builtin_amdgcn_sched_barrier(0);
-#endif
     settle_reference(s_next, key0_nxt, mask_next_tag);
   };
 
   load_ids(0);
-  fetch();
+  fetch(0, 0);
   load_ids(1);
-  // every load issued so far (Q fragments included) has landed before the loop starts, so the
-  // loop body never waits on the vector-memory counter for anything but its own prefetch
-  __builtin_amdgcn_s_waitcnt(0);
-  stage(0, 0);
   if (n_tiles > 1) {
-    fetch();
+    fetch(1, 1);
     load_ids(2);
   }
+  // everything issued so far has landed (Q fragments, tiles 0 and 1): inside the loop the
+  // vector-memory counter only ever counts the tile copies
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   qk_block(0, 0, s_next);
   settle_reference(s_next, 0, std::true_type{});
+  load_k_block(0, 1);
   int buf = 0;
-  // one tile = two steps with the staging of the next tile and the barrier between them;
-  // mask_tag says whether the blocks SETTLED in this tile (its second block and the first
-  // block of the next tile) may reach the diagonal
+  // One tile = barrier, enqueue the copy of tile + 2, two steps.  After the barrier tile + 1 is
+  // visible to every wave (it was enqueued a whole tile ago) and no wave reads tile - 1 any
+  // more, so that buffer takes tile + 2.  mask_tag says whether the blocks SETTLED in this
+  // tile (its second block and the first block of the next tile) may reach the diagonal.
   auto tile_body = [&](int tile, bool more, auto mask_tag) __attribute__((always_inline)) {
     const int buf_next = buf == 2 ? 0 : buf + 1;
-    step(buf, 0, buf, 1, tile * kTileKeys + 32, mask_tag);
-    if (more) {
-      stage(tile + 1, buf_next);
-      if (tile + 2 < n_tiles) {
-        fetch();               // K/V of tile + 2, through the ids loaded one tile ago
-        load_ids(tile + 3);
-      }
-    }
+    copies_landed();
     __syncthreads();
+    if (tile + 2 < n_tiles) {
+      fetch(tile + 2, buf == 0 ? 2 : buf - 1);   // (tile + 2) % 3, ids loaded one tile ago
+      load_ids(tile + 3);
+    }
+    // block 0: scores of block 1 (same tile), prefetch K of the next tile's block 0
+    // (on the last tile that buffer holds stale but in-bounds data nobody uses)
+    step(buf, 0, buf, 1, tile * kTileKeys + 32, buf_next, 0, mask_tag);
     if (more) {
-      step(buf, 1, buf_next, 0, (tile + 1) * kTileKeys, mask_tag);
+      // block 1: scores of the next tile's block 0, prefetch K of its block 1
+      step(buf, 1, buf_next, 0, (tile + 1) * kTileKeys, buf_next, 1, mask_tag);
     } else {
       probabilities(s_next);
       pv_block(buf, 1, s_next);
