@@ -47,12 +47,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef MC_QB
 #define MC_QB 1
 #endif
-#ifndef MC_FENCE
-#define MC_FENCE 0
-#endif
-#ifndef MC_SGB
-#define MC_SGB 0
-#endif
 #ifndef MC_KPRE
 #define MC_KPRE 2
 #endif
@@ -220,9 +214,6 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   __shared__ __attribute__((aligned(16))) char smem[3 * kStageBytes];   // three (K, V) tiles
   constexpr int kThreads = WAVES * 64;
   constexpr int kTileRows = WAVES * QB * 32;
-  constexpr int kGranules = kTileKeys * (kRowBytes / 16);     // 16-byte pieces of a K (or V) tile
-  constexpr int kFetch = kGranules / kThreads;                // pieces per thread, per K and per V
-  static_assert(kGranules % kThreads == 0, "tile must split evenly over the threads");
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -267,51 +258,71 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   // ---- global -> LDS, no registers in between.  One wave instruction writes 1 KiB of LDS (lane i
   //      its 16 bytes at +16*i): 4 tile rows x 16 granules, all inside one page.  Lane i fetches,
   //      for LDS granule position i%16 of row i/16, the logical granule (i%16) ^ swz(row).
-  //      Chunk c = wave + i*WAVES (rows 4c..4c+3, page c/4 of the tile) is this wave's i-th piece.
+  //      Only the first half of the waves issue copies: they are the first wave of each SIMD, win
+  //      the issue arbitration against the second wave and would otherwise idle at the tile
+  //      barrier, and a copy instruction holds its wave for ~130 cycles.  Fetching wave w copies
+  //      chunks w, w + kFetchWaves, ... of the tile (chunk c = rows 4c..4c+3, page c/4).
+  constexpr int kFetchWaves = WAVES / 2;
+  constexpr int kChunks = kTileKeys / 4;                      // 1 KiB chunks per K (or V) tile
+  constexpr int kFetch = kChunks / kFetchWaves;               // chunks per fetching wave
+  static_assert(kChunks % kFetchWaves == 0 && kFetch <= 8, "tile must split evenly over the fetching waves");
   const char* kbase = reinterpret_cast<const char*>(a.k_pool) + (int64_t)item.kv_head * kPageHeadBytes;
   const char* vbase = reinterpret_cast<const char*>(a.v_pool) + (int64_t)item.kv_head * kPageHeadBytes;
   const int64_t page_stride = (int64_t)a.Hkv * kPageHeadBytes;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  const int wave_page = wave_u >> 2;                         // page of the tile this wave's first chunk lies in
+  const bool fetcher = wave_u < kFetchWaves;
   // The block table is read through the scalar cache (it is constant while the kernel runs),
   // one tile AHEAD of the K/V loads that need it, so no wave ever waits for a page id.
   typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
   const_i32_ptr btc = (const_i32_ptr)(a.block_tables + (int64_t)item.req * a.max_pages);
   const int64_t first_page_off = (int64_t)btc[0] * page_stride;   // page of key 0: always valid
   int pid[kFetch];
-  uint32_t k_src[kFetch], v_src[kFetch];   // byte offset inside the (page, head) block each lane copies from
-  int tile_row[kFetch];
-#pragma unroll
-  for (int i = 0; i < kFetch; ++i) {
-    const int row = (wave_u + i * WAVES) * 4 + (lane >> 4);
-    const int pg = lane & 15;
-    tile_row[i] = row;
-    k_src[i] = (uint32_t)((row & 15) * kRowBytes + ((pg ^ T::k_swz(row)) << 4));
-    v_src[i] = (uint32_t)((row & 15) * kRowBytes + ((pg ^ T::v_swz(row)) << 4));
-  }
 
   auto load_ids = [&](int tile) __attribute__((always_inline)) {
+    if (!fetcher) return;
 #pragma unroll
     for (int i = 0; i < kFetch; ++i) {
-      int lp = tile * (kTileKeys / kPageTokens) + i * (WAVES / 4) + wave_page;
+      int lp = tile * (kTileKeys / kPageTokens) + (wave_u + i * kFetchWaves) / 4;
       lp = lp < last_page ? lp : last_page;                  // never index the table past the request's pages
       pid[i] = btc[lp];
     }
   };
+  // Per-lane byte offset inside a (page, head) block: the same for every chunk of a wave, because
+  // a wave's chunks are 16 rows (one page) apart and both swizzles depend on row % 16 only.
+  const int lane_row = (wave_u & 3) * 4 + (lane >> 4);       // row of the page this lane copies a granule of
+  const uint32_t k_src = (uint32_t)(lane_row * kRowBytes + (((lane & 15) ^ T::k_swz(lane_row)) << 4));
+  const uint32_t v_src = (uint32_t)(lane_row * kRowBytes + (((lane & 15) ^ T::v_swz(lane_row)) << 4));
+  static_assert(kFetchWaves % 4 == 0, "a fetching wave's chunks must all sit at the same rows of their pages");
   // enqueue the copy of tile `tile` (page ids in pid[]) into LDS buffer `buf`
   auto fetch = [&](int tile, int buf) __attribute__((always_inline)) {
+    if (!fetcher) return;
+    char* dst0 = smem + buf * kStageBytes + wave_u * 1024;
+    if ((tile + 1) * kTileKeys <= L) {
+      // whole tile inside the sequence: scalar page base + constant lane offset
 #pragma unroll
-    for (int i = 0; i < kFetch; ++i) {
+      for (int i = 0; i < kFetch; ++i) {
+        const int64_t page_off = (int64_t)pid[i] * page_stride;
+        char* dst = dst0 + i * kFetchWaves * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + page_off + k_src),
+                                         (MC_LDS void*)dst, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + page_off + v_src),
+                                         (MC_LDS void*)(dst + kKTileBytes), 16, 0, 0);
+      }
+    } else {
       // Slots at or past the request's length may hold anything (NaN would survive p = 0 in P V):
       // those lanes copy row 0 of the request's first page instead; the causal mask hides the key.
-      const bool in_seq = tile * kTileKeys + tile_row[i] < L;
-      const int64_t page_off = (int64_t)pid[i] * page_stride;
-      const char* ks = kbase + (in_seq ? page_off + k_src[i] : first_page_off + (k_src[i] & 255));
-      const char* vs = vbase + (in_seq ? page_off + v_src[i] : first_page_off + (v_src[i] & 255));
-      char* dst = smem + buf * kStageBytes + (wave_u + i * WAVES) * 1024;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ks, (MC_LDS void*)dst, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)vs,
-                                       (MC_LDS void*)(dst + kKTileBytes), 16, 0, 0);
+#pragma unroll
+      for (int i = 0; i < kFetch; ++i) {
+        const int row = (wave_u + i * kFetchWaves) * 4 + (lane >> 4);
+        const bool in_seq = tile * kTileKeys + row < L;
+        const int64_t page_off = (int64_t)pid[i] * page_stride;
+        const char* ks = kbase + (in_seq ? page_off + k_src : first_page_off + (k_src & 255));
+        const char* vs = vbase + (in_seq ? page_off + v_src : first_page_off + (v_src & 255));
+        char* dst = dst0 + i * kFetchWaves * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ks, (MC_LDS void*)dst, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)vs,
+                                         (MC_LDS void*)(dst + kKTileBytes), 16, 0, 0);
+      }
     }
   };
   // wait until this wave's copies have landed (vmcnt(0); the other counters are left alone)
