@@ -216,14 +216,19 @@ def main():
                                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                                           "us_per_layer": round(us, 2), "bytes_per_launch": copy_bytes,
                                           "traffic": hbm(name)}
-        if args.attn_config != 3:
-            del attn.q, attn.k, attn.v, attn.out
-            long_ctx = Attn(3)
-            med, mn = long_ctx.time_isolated()
-            result["attn_config3"] = {"workload": "config 3: 8/1 heads, P=122880, C=8192 (128k context)",
-                                      "flops": long_ctx.flops, "ms_median": round(med, 4), "ms_min": round(mn, 4),
-                                      "tflops": round(long_ctx.flops / (med * 1e-3) / 1e12, 2),
-                                      "pct_mfma_peak": round(100 * long_ctx.flops / (med * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2)}
+        labels = {3: "config 3: 8/1 heads, P=122880, C=8192 (128k context)",
+                  4: "config 4: 16 requests, 64/8 heads, prefixes U[0,32768] (page multiples), chunks lognormal(median 2048)"}
+        del attn.q, attn.k, attn.v, attn.out
+        for idx in (3, 4):
+            if idx == args.attn_config:
+                continue
+            other = Attn(idx)
+            med, mn = other.time_isolated(iters=6 if idx == 4 else 10)
+            result[f"attn_config{idx}"] = {"workload": labels[idx], "flops": other.flops, "ms_median": round(med, 4),
+                                          "ms_min": round(mn, 4), "tflops": round(other.flops / (med * 1e-3) / 1e12, 2),
+                                          "pct_mfma_peak": round(100 * other.flops / (med * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2)}
+            del other
+            torch.cuda.empty_cache()
 
     if args.cpu_rows > 0:
         # the CPU oracle, as it stands, on a bounded sample of the same attention workload
