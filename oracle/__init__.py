@@ -50,6 +50,8 @@ def _load():
         for f in (lib.mco_kv_pack_layer, lib.mco_kv_unpack_layer):
             f.restype = ctypes.c_int
             f.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, i32]
+        lib.mco_kv_append_paged.restype = ctypes.c_int
+        lib.mco_kv_append_paged.argtypes = [vp, vp, vp, vp, i64, vp, i32, vp, vp, i32, i32, i32, i64]
         _lib = lib
     return _lib
 
@@ -169,3 +171,22 @@ def kv_unpack_layer(k_in: np.ndarray, v_in: np.ndarray, page_ids, k_pool: np.nda
     rc = lib.mco_kv_unpack_layer(_ptr(k_in), _ptr(v_in), N, pb, _ptr(ids), n, _ptr(k_pool), _ptr(v_pool), threads)
     if rc != 0:
         raise ValueError("page id outside the pool")
+
+
+def kv_append_paged(k_new: np.ndarray, v_new: np.ndarray, k_pool: np.ndarray, v_pool: np.ndarray,
+                    block_tables, prefix_lens, new_lens) -> None:
+    """Write new tokens' K/V rows [total_new, Hkv, D] into their page slots of pools [N, Hkv, S, D], in place."""
+    lib = _load()
+    assert k_pool.flags.c_contiguous and v_pool.flags.c_contiguous and k_pool.shape == v_pool.shape
+    N, Hkv, S, D = k_pool.shape
+    k_new = np.ascontiguousarray(k_new)
+    v_new = np.ascontiguousarray(v_new)
+    assert k_new.dtype == k_pool.dtype and v_new.dtype == v_pool.dtype
+    bt = np.ascontiguousarray(block_tables, dtype=np.int32)
+    pl = np.ascontiguousarray(prefix_lens, dtype=np.int32)
+    nl = np.ascontiguousarray(new_lens, dtype=np.int32)
+    assert k_new.shape == (int(nl.sum()), Hkv, D) and v_new.shape == k_new.shape
+    rc = lib.mco_kv_append_paged(_ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool), N, _ptr(bt), bt.shape[1],
+                                 _ptr(pl), _ptr(nl), pl.shape[0], Hkv, S, D * k_pool.itemsize)
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")

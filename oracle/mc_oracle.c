@@ -234,3 +234,37 @@ int mco_kv_unpack_layer(const uint8_t* k_in, const uint8_t* v_in, int64_t num_pa
   }
   return 0;
 }
+
+/*
+ * Incremental prefill "stores the newly generated incremental KVCache" (Section 3, step 2):
+ * token i of request r (absolute position P_r + i) goes to slot (P_r + i) % S of page
+ * block_table[r][(P_r + i) / S], for every KV head, bytes verbatim.  k_new / v_new are
+ * [total_new, Hkv, row_bytes], pools are [N, Hkv, S, row_bytes].  Slots not written keep
+ * their bytes.  Returns -1 on a bad argument (nothing written).
+ */
+int mco_kv_append_paged(const uint8_t* k_new, const uint8_t* v_new, uint8_t* k_pool, uint8_t* v_pool,
+                        int64_t num_pages, const int32_t* block_tables, int max_pages_per_req,
+                        const int32_t* prefix_lens, const int32_t* new_lens, int batch, int Hkv, int S,
+                        int64_t row_bytes) {
+  for (int r = 0; r < batch; ++r) {
+    if (prefix_lens[r] < 0 || new_lens[r] < 0) return -1;
+    if (new_lens[r] > 0 && (int64_t)max_pages_per_req * S < (int64_t)prefix_lens[r] + new_lens[r]) return -1;
+    for (int i = 0; i < new_lens[r]; ++i) {
+      int64_t page = block_tables[(int64_t)r * max_pages_per_req + (prefix_lens[r] + i) / S];
+      if (page < 0 || page >= num_pages) return -1;
+    }
+  }
+  int64_t t = 0;
+  for (int r = 0; r < batch; ++r)
+    for (int i = 0; i < new_lens[r]; ++i, ++t) {
+      const int64_t pos = (int64_t)prefix_lens[r] + i;
+      const int64_t page = block_tables[(int64_t)r * max_pages_per_req + pos / S];
+      for (int g = 0; g < Hkv; ++g) {
+        const int64_t dst = ((page * Hkv + g) * S + pos % S) * row_bytes;
+        const int64_t src = (t * Hkv + g) * row_bytes;
+        memcpy(k_pool + dst, k_new + src, (size_t)row_bytes);
+        memcpy(v_pool + dst, v_new + src, (size_t)row_bytes);
+      }
+    }
+  return 0;
+}
