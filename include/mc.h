@@ -106,6 +106,32 @@ mc_status mc_prefill_attn_paged(const mc_attn_params* p, const void* q, const vo
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Bytes of device workspace mc_kv_append_paged needs (the per-request table).  0 for batch < 0.
+ */
+size_t mc_kv_append_workspace_bytes(int32_t batch);
+
+/*
+ * Store the new chunk's K/V into the request's pages (Section 3, step 2: incremental prefill
+ * keeps the newly generated KVCache; this is what puts it where mc_prefill_attn_paged reads it).
+ * Token i of request r (absolute position P_r + i) is written, for every KV head g, to
+ * pool[block_tables[r][(P_r + i) / S]][g][(P_r + i) % S][:], bytes verbatim.
+ *
+ *   k_new, v_new  dev  [total_new_tokens, Hkv, D]  requests back to back, dtype p->dtype
+ *   k_pool,v_pool dev  [N, Hkv, S, D]              written in place; other slots keep their bytes
+ *   block_tables  dev  [batch, max_pages_per_req]
+ *   prefix_lens, new_lens  host [batch]
+ *   workspace     dev  >= mc_kv_append_workspace_bytes(batch), 16-byte aligned
+ *
+ * Same shape restrictions and status codes as mc_prefill_attn_paged (num_q_heads is only
+ * checked for divisibility).  Two requests whose block tables name the same page for
+ * positions both write: undefined which wins.
+ */
+mc_status mc_kv_append_paged(const mc_attn_params* p, const void* k_new, const void* v_new, void* k_pool,
+                             void* v_pool, const int32_t* block_tables, int32_t max_pages_per_req,
+                             const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Store path of layer-wise prefill (Section 5.2): gather pages of one layer's
  * scattered pools into contiguous buffers, page i of the output = page
  * page_ids[i] of the pool, bytes verbatim.

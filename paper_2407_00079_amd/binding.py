@@ -19,7 +19,7 @@ MC_ERR_NULL, MC_ERR_SHAPE, MC_ERR_UNSUPPORTED, MC_ERR_ALIGN, MC_ERR_RANGE, MC_ER
 MC_DTYPE_BF16, MC_DTYPE_F32 = 0, 1
 
 EXPORTS = ("mc_status_string", "mc_prefill_attn_workspace_bytes", "mc_prefill_attn_paged",
-           "mc_kv_pack_layer", "mc_kv_unpack_layer")
+           "mc_kv_pack_layer", "mc_kv_unpack_layer", "mc_kv_append_workspace_bytes", "mc_kv_append_paged")
 
 
 class McAttnParams(ctypes.Structure):
@@ -60,6 +60,11 @@ def lib():
         for f in (l.mc_kv_pack_layer, l.mc_kv_unpack_layer):
             f.restype = ctypes.c_int
             f.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, vp]
+        l.mc_kv_append_workspace_bytes.restype = ctypes.c_size_t
+        l.mc_kv_append_workspace_bytes.argtypes = [i32]
+        l.mc_kv_append_paged.restype = ctypes.c_int
+        l.mc_kv_append_paged.argtypes = [ctypes.POINTER(McAttnParams), vp, vp, vp, vp, vp, i32, vp, vp, i32, vp,
+                                         ctypes.c_size_t, vp]
         _lib = l
     return _lib
 
@@ -134,6 +139,33 @@ def mc_kv_unpack_layer(k_in, v_in, num_pages: int, page_bytes: int, page_ids, n:
                                 _dev_ptr(k_pool_layer), _dev_ptr(v_pool_layer), _stream_handle(stream))
     if st != MC_OK:
         raise McError(st, "mc_kv_unpack_layer")
+
+
+def mc_kv_append_workspace_bytes(batch: int) -> int:
+    return int(lib().mc_kv_append_workspace_bytes(batch))
+
+
+def mc_kv_append_paged_raw(params, k_new, v_new, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens,
+                           new_lens, batch, workspace, workspace_bytes, hip_stream) -> int:
+    return int(lib().mc_kv_append_paged(ctypes.byref(params) if params is not None else None, k_new, v_new, k_pool,
+                                        v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens, batch,
+                                        workspace, workspace_bytes, hip_stream))
+
+
+def mc_kv_append_paged(params: McAttnParams, k_new, v_new, k_pool, v_pool, block_tables, prefix_lens, new_lens,
+                       workspace, stream=None) -> None:
+    """Enqueue the scatter of the new tokens' K/V rows into their page slots (torch device tensors)."""
+    batch = len(prefix_lens)
+    pl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in prefix_lens])
+    nl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in new_lens])
+    max_pages = int(block_tables.shape[1]) if block_tables is not None and block_tables.dim() == 2 else 0
+    ws_bytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    st = mc_kv_append_paged_raw(params, _dev_ptr(k_new), _dev_ptr(v_new), _dev_ptr(k_pool), _dev_ptr(v_pool),
+                                _dev_ptr(block_tables), max_pages, ctypes.cast(pl, ctypes.c_void_p),
+                                ctypes.cast(nl, ctypes.c_void_p), batch, _dev_ptr(workspace), ws_bytes,
+                                _stream_handle(stream))
+    if st != MC_OK:
+        raise McError(st, "mc_kv_append_paged")
 
 
 def attn_params(num_q_heads: int, num_kv_heads: int, head_dim: int, page_size: int, num_pages: int,

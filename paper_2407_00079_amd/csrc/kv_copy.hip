@@ -52,7 +52,47 @@ __global__ __launch_bounds__(kThreads) void kv_copy_kernel(const u32x4* __restri
   }
 }
 
+// Append (paper Section 3 step 2: the chunk's new KVCache is kept in the request's pages):
+// one thread moves one 16-byte granule of one (token, KV head) row of K and of V.  The request
+// of a token is found by bisection of the per-request table; rows are 256 bytes for both dtypes.
+__global__ __launch_bounds__(256) void kv_append_kernel(const u32x4* __restrict__ k_new, const u32x4* __restrict__ v_new,
+                                                        u32x4* __restrict__ k_pool, u32x4* __restrict__ v_pool,
+                                                        const int32_t* __restrict__ block_tables, int32_t max_pages,
+                                                        const AttnReq* __restrict__ reqs, int32_t batch,
+                                                        int64_t total_vecs, int32_t Hkv) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total_vecs) return;
+  const int gran = (int)(idx & 15);
+  const int64_t row = idx >> 4;                 // (token, head)
+  const int g = (int)(row % Hkv);
+  const int32_t tok = (int32_t)(row / Hkv);
+  int lo = 0, hi = batch - 1;                   // last request with q_off <= tok and at least one token
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (reqs[mid].q_off <= tok) lo = mid; else hi = mid - 1;
+  }
+  // requests without new tokens share their q_off with the next one: bisection lands on the
+  // last of such a run, which is the one that owns the token
+  const AttnReq rq = reqs[lo];
+  const int32_t pos = rq.prefix + (tok - rq.q_off);
+  const int64_t page = block_tables[(int64_t)lo * max_pages + (pos >> 4)];
+  const int64_t dst = (((page * Hkv + g) << 4) + (pos & 15)) * 16 + gran;
+  k_pool[dst] = k_new[idx];
+  v_pool[dst] = v_new[idx];
+}
+
 }  // namespace
+
+hipError_t launch_kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
+                            const int32_t* block_tables, int32_t max_pages, const AttnReq* reqs, int32_t batch,
+                            int64_t total_new, int32_t Hkv, hipStream_t stream) {
+  const int64_t total_vecs = total_new * Hkv * 16;
+  (void)hipGetLastError();
+  kv_append_kernel<<<(unsigned)((total_vecs + 255) / 256), 256, 0, stream>>>(
+      (const u32x4*)k_new, (const u32x4*)v_new, (u32x4*)k_pool, (u32x4*)v_pool, block_tables, max_pages, reqs, batch,
+      total_vecs, Hkv);
+  return hipGetLastError();
+}
 
 int kv_copy_slice_vecs() { return kSliceVecs; }
 

@@ -238,6 +238,58 @@ mc_status mc_prefill_attn_paged(const mc_attn_params* p, const void* q, const vo
   return MC_OK;
 }
 
+size_t mc_kv_append_workspace_bytes(int32_t batch) {
+  return batch < 0 ? 0 : sizeof(mc::AttnReq) * (size_t)batch + 64;
+}
+
+mc_status mc_kv_append_paged(const mc_attn_params* p, const void* k_new, const void* v_new, void* k_pool,
+                             void* v_pool, const int32_t* block_tables, int32_t max_pages_per_req,
+                             const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+  mc_status st = check_params(p);
+  if (st != MC_OK) return st;
+  if (batch < 0 || max_pages_per_req < 0) return MC_ERR_SHAPE;
+  if (batch == 0) return MC_OK;
+  if (prefix_lens == nullptr || new_lens == nullptr) return MC_ERR_NULL;
+  int64_t total_new = 0;
+  for (int32_t r = 0; r < batch; ++r) {
+    if (prefix_lens[r] < 0 || new_lens[r] < 0) return MC_ERR_SHAPE;
+    const int64_t len = (int64_t)prefix_lens[r] + new_lens[r];
+    if (len > INT32_MAX - 1024) return MC_ERR_RANGE;
+    if (new_lens[r] > 0 && (int64_t)max_pages_per_req * p->page_size < len) return MC_ERR_SHAPE;
+    total_new += new_lens[r];
+  }
+  if (total_new == 0) return MC_OK;
+  if (k_new == nullptr || v_new == nullptr || k_pool == nullptr || v_pool == nullptr || block_tables == nullptr)
+    return MC_ERR_NULL;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(workspace) ||
+      (reinterpret_cast<uintptr_t>(block_tables) & 3u))
+    return MC_ERR_ALIGN;
+  if (total_new > INT32_MAX || total_new * p->num_kv_heads * 16 / 256 + 1 > INT32_MAX ||
+      (int64_t)batch * max_pages_per_req > INT32_MAX)
+    return MC_ERR_RANGE;
+  if (workspace == nullptr || workspace_bytes < mc_kv_append_workspace_bytes(batch)) return MC_ERR_WORKSPACE;
+
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  const size_t up_bytes = sizeof(mc::AttnReq) * (size_t)batch;
+  int slot = -1;
+  mc::AttnReq* host = reinterpret_cast<mc::AttnReq*>(g_staging.acquire(up_bytes, &slot));
+  if (host == nullptr) return MC_ERR_HIP;
+  int64_t q_off = 0;
+  for (int32_t r = 0; r < batch; ++r) {
+    host[r] = {(int32_t)q_off, prefix_lens[r], new_lens[r],
+               (int32_t)(((int64_t)prefix_lens[r] + new_lens[r] + p->page_size - 1) / p->page_size)};
+    q_off += new_lens[r];
+  }
+  if (hipMemcpyAsync(workspace, host, up_bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
+  if (!g_staging.release_after(slot, stream)) return MC_ERR_HIP;
+  if (mc::launch_kv_append(k_new, v_new, k_pool, v_pool, block_tables, max_pages_per_req,
+                           reinterpret_cast<const mc::AttnReq*>(workspace), batch, total_new, p->num_kv_heads,
+                           stream) != hipSuccess)
+    return MC_ERR_HIP;
+  return MC_OK;
+}
+
 static mc_status check_copy(const void* a, const void* b, int64_t num_pages, int64_t page_bytes, const int32_t* ids,
                             int64_t n, const void* c, const void* d) {
   if (num_pages < 0 || page_bytes < 0 || n < 0) return MC_ERR_SHAPE;

@@ -51,4 +51,9 @@ int kv_copy_slice_vecs();
 hipError_t launch_kv_copy(bool pack, const void* k_src, const void* v_src, void* k_dst, void* v_dst,
                           const int32_t* page_ids, int64_t n, int64_t page_bytes, hipStream_t stream);
 
+// enqueue the scatter of total_new tokens' K/V rows (256 bytes per KV head) into their page slots
+hipError_t launch_kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
+                            const int32_t* block_tables, int32_t max_pages, const AttnReq* reqs, int32_t batch,
+                            int64_t total_new, int32_t Hkv, hipStream_t stream);
+
 }  // namespace mc

@@ -1,0 +1,109 @@
+"""GPU parity: mc_kv_append_paged against the CPU oracle, byte for byte, and attention over the appended pools."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_00079_amd import binding as B
+from paper_2407_00079_amd import workloads as W
+
+from append_util import empty_chunk_pools, new_rows
+from gpu_util import DeviceCase, check_close, dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _append(case, k_new, v_new, k_dev, v_dev, prefix_lens, new_lens, bt_dev=None):
+    params = B.attn_params(case.num_q_heads, case.num_kv_heads, case.head_dim, case.page_size, case.num_pages,
+                           case.dtype)
+    ws = torch.empty(max(B.mc_kv_append_workspace_bytes(len(prefix_lens)), 16), dtype=torch.uint8, device="cuda:0")
+    bt = dev(case.block_tables) if bt_dev is None else bt_dev
+    B.mc_kv_append_paged(params, dev(k_new), dev(v_new), k_dev, v_dev, bt, list(prefix_lens), list(new_lens), ws)
+    torch.cuda.synchronize()
+
+
+def _host(t, like):
+    return t.cpu().numpy().view(like.dtype)
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,D,prefix,new,pages", [
+    (W.BF16, 4, 2, 128, [37, 0, 16, 5], [50, 33, 1, 0], 64),         # unaligned prefixes, mid-page end, empty request
+    (W.F32, 2, 1, 64, [3], [29], 8),                                  # the fp32 row shape
+    (W.BF16, 8, 8, 128, [0, 0, 0], [0, 0, 700], 80),                  # empty requests ahead of the only chunk
+    (W.BF16, 64, 8, 128, [1000, 15, 4097], [513, 1, 255], 512),       # LLaMA2-70B heads, several blocks and a ragged tail
+    (W.BF16, 2, 1, 128, [5] * 40, [1] * 40, 64),                      # many one-token requests (decode-shaped)
+])
+def test_append_matches_oracle(oracle, dtype, Hq, Hkv, D, prefix, new, pages):
+    print(f"append case {dtype} Hq={Hq} Hkv={Hkv} prefix={prefix[:4]} new={new[:4]}", flush=True)
+    case = W.make_attn_case(21, dtype, Hq, Hkv, D, 16, prefix, new, pages, keep_logical=True)
+    k0, v0 = empty_chunk_pools(case)
+    k_new, v_new = new_rows(case)
+    k_dev, v_dev = dev(k0), dev(v0)
+    _append(case, k_new, v_new, k_dev, v_dev, prefix, new)
+    oracle.kv_append_paged(k_new, v_new, k0, v0, case.block_tables, prefix, new)
+    np.testing.assert_array_equal(_host(k_dev, k0).view(np.uint8), k0.view(np.uint8))
+    np.testing.assert_array_equal(_host(v_dev, v0).view(np.uint8), v0.view(np.uint8))
+
+
+def test_append_in_two_chunks_then_attention(oracle):
+    # store the chunk in two calls (the second starts mid page), then attend over the pools the GPU wrote
+    case = W.make_attn_case(22, W.BF16, 8, 2, 128, 16, [70, 0], [300, 129], 64, keep_logical=True)
+    k0, v0 = empty_chunk_pools(case)
+    k_new, v_new = new_rows(case)
+    k_dev, v_dev = dev(k0), dev(v0)
+    first = [155, 40]
+    off = case.q_offsets
+    a = np.concatenate([np.arange(off[r], off[r] + first[r]) for r in range(2)])
+    b = np.concatenate([np.arange(off[r] + first[r], off[r] + case.new_lens[r]) for r in range(2)])
+    _append(case, k_new[a], v_new[a], k_dev, v_dev, case.prefix_lens.tolist(), first)
+    _append(case, k_new[b], v_new[b], k_dev, v_dev, [70 + 155, 40], [300 - 155, 129 - 40])
+    np.testing.assert_array_equal(_host(k_dev, k0), case.k_pool)
+    np.testing.assert_array_equal(_host(v_dev, v0), case.v_pool)
+    dc = DeviceCase(case)
+    dc.k_pool, dc.v_pool = k_dev, v_dev
+    dc.run()
+    out, lse = dc.result()
+    ref_out, ref_lse, _ = oracle.case_full(case)
+    check_close(out, ref_out, W.BF16, "attention over appended pools")
+    assert np.abs(lse - ref_lse).max() <= 2e-3
+
+
+def test_append_full_size_chunk(oracle):
+    # one 8192-token chunk at the LLaMA2-70B KV shape behind a 16k prefix: sampled pages against the oracle's write
+    P, C, Hkv = 16384, 8192, 8
+    pages = (P + C) // 16
+    rng = np.random.default_rng(5)
+    bt = rng.permutation(pages + 100)[:pages].astype(np.int32).reshape(1, -1)
+    k_new = rng.integers(0, 1 << 16, size=(C, Hkv, 128), dtype=np.uint16)
+    v_new = rng.integers(0, 1 << 16, size=(C, Hkv, 128), dtype=np.uint16)
+    k_dev = torch.zeros((pages + 100, Hkv, 16, 128), dtype=torch.int16, device="cuda:0")
+    v_dev = torch.zeros_like(k_dev)
+    params = B.attn_params(64, Hkv, 128, 16, pages + 100, W.BF16)
+    ws = torch.empty(B.mc_kv_append_workspace_bytes(1), dtype=torch.uint8, device="cuda:0")
+    B.mc_kv_append_paged(params, dev(k_new), dev(v_new), k_dev, v_dev, dev(bt), [P], [C], ws)
+    torch.cuda.synchronize()
+    k0 = np.zeros((pages + 100, Hkv, 16, 128), dtype=np.uint16)
+    v0 = np.zeros_like(k0)
+    oracle.kv_append_paged(k_new, v_new, k0, v0, bt, [P], [C])
+    np.testing.assert_array_equal(k_dev.cpu().numpy().view(np.uint16), k0)
+    np.testing.assert_array_equal(v_dev.cpu().numpy().view(np.uint16), v0)
+
+
+def test_append_rejections_launch_nothing():
+    case = W.make_attn_case(23, W.BF16, 2, 1, 128, 16, [8], [8], 4, keep_logical=True)
+    k_new, v_new = new_rows(case)
+    k_dev, v_dev = dev(case.k_pool), dev(case.v_pool)
+    params = B.attn_params(2, 1, 128, 16, 4, W.BF16)
+    ws = torch.empty(64, dtype=torch.uint8, device="cuda:0")
+    bt = dev(case.block_tables)
+    with pytest.raises(B.McError) as e:       # block table too short for P + C
+        B.mc_kv_append_paged(params, dev(k_new), dev(v_new), k_dev, v_dev, bt[:, :0].reshape(1, 0), [8], [8], ws)
+    assert e.value.status == B.MC_ERR_SHAPE
+    with pytest.raises(B.McError) as e:
+        B.mc_kv_append_paged(params, dev(k_new), dev(v_new), k_dev, v_dev, bt, [8], [8], None)
+    assert e.value.status == B.MC_ERR_WORKSPACE
+    with pytest.raises(B.McError) as e:
+        B.mc_kv_append_paged(params, None, dev(v_new), k_dev, v_dev, bt, [8], [8], ws)
+    assert e.value.status == B.MC_ERR_NULL
+    B.mc_kv_append_paged(params, None, None, k_dev, v_dev, bt, [8], [0], ws)     # nothing to store: fine
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(k_dev.cpu().numpy().view(np.uint16), case.k_pool)

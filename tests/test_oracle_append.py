@@ -4,24 +4,7 @@ import pytest
 
 from paper_2407_00079_amd import workloads as W
 
-
-def empty_chunk_pools(case):
-    """Pools as they are BEFORE the chunk is appended: the chunk's slots hold a marker, everything else as built."""
-    k, v = case.k_pool.copy(), case.v_pool.copy()
-    marker = np.array(0x1234 if case.dtype == W.BF16 else 7.25).astype(k.dtype)
-    for r in range(case.batch):
-        P, C = int(case.prefix_lens[r]), int(case.new_lens[r])
-        for pos in range(P, P + C):
-            pg = case.block_tables[r, pos // case.page_size]
-            k[pg, :, pos % case.page_size, :] = marker
-            v[pg, :, pos % case.page_size, :] = marker
-    return k, v
-
-
-def new_rows(case):
-    k_new = np.concatenate([case.k_logical[r][int(case.prefix_lens[r]):] for r in range(case.batch)])
-    v_new = np.concatenate([case.v_logical[r][int(case.prefix_lens[r]):] for r in range(case.batch)])
-    return k_new, v_new
+from append_util import empty_chunk_pools, new_rows
 
 
 @pytest.mark.parametrize("dtype,D", [(W.BF16, 128), (W.F32, 64)])
