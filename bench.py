@@ -216,6 +216,32 @@ def main():
                                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                                           "us_per_layer": round(us, 2), "bytes_per_launch": copy_bytes,
                                           "traffic": hbm(name)}
+        # append of the step's chunk: its new K/V rows (already in the pools' pages) scattered from a contiguous copy
+        c = attn.case
+        if all(x > 0 for x in attn.nl[:1]):
+            row = c.head_dim * 2
+            n_rows = c.total_new * c.num_kv_heads
+            k_new = torch.randint(-32768, 32767, (c.total_new, c.num_kv_heads, c.head_dim), dtype=torch.int16, device=dev)
+            v_new = torch.randint(-32768, 32767, (c.total_new, c.num_kv_heads, c.head_dim), dtype=torch.int16, device=dev)
+            aws = torch.empty(B.mc_kv_append_workspace_bytes(c.batch), dtype=torch.uint8, device=dev)
+            kp2, vp2 = attn.k.clone(), attn.v.clone()
+            for _ in range(5):
+                B.mc_kv_append_paged(attn.params, k_new, v_new, kp2, vp2, attn.bt, attn.pl, attn.nl, aws, s)
+            reps = 80
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(s)
+            for i in range(reps):
+                B.mc_kv_append_paged(attn.params, k_new, v_new, kp2, vp2, attn.bt, attn.pl, attn.nl, aws, s)
+            b.record(s)
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / reps
+            ab = 2 * 2 * n_rows * row
+            result["roofline_append"] = {"kernel": "kv_append_kernel", "bound": "hbm",
+                                         "achieved": round(ab / (us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                         "frac": round(ab / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "us_per_launch": round(us, 2),
+                                         "bytes_per_launch": ab, "traffic": None,
+                                         "note": "same buffers every launch: the working set fits the 256 MiB last-level cache"}
+            del k_new, v_new, kp2, vp2
         labels = {3: "config 3: 8/1 heads, P=122880, C=8192 (128k context)",
                   4: "config 4: 16 requests, 64/8 heads, prefixes U[0,32768] (page multiples), chunks lognormal(median 2048)"}
         del attn.q, attn.k, attn.v, attn.out

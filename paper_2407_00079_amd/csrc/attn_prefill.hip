@@ -47,6 +47,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef MC_QB
 #define MC_QB 1
 #endif
+#ifndef MC_KRING
+#define MC_KRING 0
+#endif
 #ifndef MC_KPRE
 #define MC_KPRE 2
 #endif
@@ -130,24 +133,30 @@ struct Bf16 {
     bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(p + 8 * kRowBytes));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
-  // B operand: probabilities of accumulator registers 8*step .. 8*step+7
-  static __device__ __forceinline__ frag make_p(const f32x16& p, int step) {
-    frag f;
+  // A block's probabilities as P V multiplies them: rounded to bf16, fragment `step` holds the
+  // accumulator registers 8*step .. 8*step+7 (the B operand of that 16-key step).
+  struct pblock { frag f[kPVSteps]; };
+  static __device__ __forceinline__ pblock round_p(const f32x16& p) {
+    pblock b;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) f[e] = (__bf16)p[step * 8 + e];
-    return f;
+    for (int st = 0; st < kPVSteps; ++st)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) b.f[st][e] = (__bf16)p[st * 8 + e];
+    return b;
   }
-  // sum of a block's 16 probabilities AS ROUNDED to bf16 (the values P V multiplies), two per
-  // v_dot2c_f32_bf16 with fp32 accumulation; the conversions are the ones make_p needs anyway
-  static __device__ __forceinline__ float block_sum(const f32x16& p) {
+  static __device__ __forceinline__ frag p_frag(const pblock& b, int step) { return b.f[step]; }
+  // sum of the 16 ROUNDED probabilities, two per v_dot2c_f32_bf16 with fp32 accumulation
+  static __device__ __forceinline__ float block_sum(const pblock& b) {
     typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
     float acc = 0.f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const bf16x2 pr = {(__bf16)p[2 * e], (__bf16)p[2 * e + 1]};
-      acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
-    }
+    for (int st = 0; st < kPVSteps; ++st)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bf16x2 pr = {b.f[st][2 * e], b.f[st][2 * e + 1]};
+        acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
+      }
     return acc;
   }
   // four consecutive output columns
@@ -193,11 +202,13 @@ struct F32 {
     return *reinterpret_cast<MC_LDS const float*>(vt_lane + (kb * 32 + (step >> 2) * 8 + (step & 3)) * kRowBytes +
                                                   db * 128);
   }
-  static __device__ __forceinline__ frag make_p(const f32x16& p, int step) { return p[step]; }
-  static __device__ __forceinline__ float block_sum(const f32x16& p) {
+  struct pblock { f32x16 p; };
+  static __device__ __forceinline__ pblock round_p(const f32x16& p) { return pblock{p}; }
+  static __device__ __forceinline__ frag p_frag(const pblock& b, int step) { return b.p[step]; }
+  static __device__ __forceinline__ float block_sum(const pblock& b) {
     float acc = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc += p[r];
+    for (int r = 0; r < 16; ++r) acc += b.p[r];
     return acc;
   }
   static __device__ __forceinline__ void store4(char* orow, int col, float a, float b, float c, float d) {
@@ -396,24 +407,31 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
       }
     }
   };
-  // (2) scores -> probabilities relative to the settled reference, in place; straight-line code
-  auto probabilities = [&](f32x16 (&s)[QB]) {
+  // (2) scores -> probabilities relative to the reference, in the form P V multiplies; straight-line
+  //     code.  bsum: this lane's share of each column's sum over the block.
+  auto probabilities = [&](const f32x16 (&s)[QB], typename T::pblock (&pb)[QB], float (&bsum)[QB]) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       const float m_ref = m_run[qb];
+      f32x16 p;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[qb][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][r], c, -m_ref));
-      l_sum[qb] += T::block_sum(s[qb]);
+      for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][r], c, -m_ref));
+      pb[qb] = T::round_p(p);
+      bsum[qb] = T::block_sum(pb[qb]);
     }
   };
+  auto add_sums = [&](const float (&bsum)[QB]) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) l_sum[qb] += bsum[qb];
+  };
   // O^T += V^T P^T for the block's 32 keys
-  auto pv_block = [&](int buf, int kb, const f32x16 (&s)[QB]) {
+  auto pv_block = [&](int buf, int kb, const typename T::pblock (&pb)[QB]) {
     const uint32_t vt = v_lane + buf * kStageBytes;
 #pragma unroll
     for (int st = 0; st < T::kPVSteps; ++st) {
       typename T::frag pf[QB];
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) pf[qb] = T::make_p(s[qb], st);
+      for (int qb = 0; qb < QB; ++qb) pf[qb] = T::p_frag(pb[qb], st);
 #pragma unroll
       for (int db = 0; db < T::kDBlocks; ++db) {
         const typename T::frag vf = T::load_v(vt, kb, st, db);
@@ -440,9 +458,22 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   };
   // One step: scores of block j+1 from the K fragments fetched during the previous step,
   // probabilities and P V of block j, then the K fragments of block j+2 (their LDS latency
-  // is covered by a whole step), then the reference check for block j+1.
+  // is covered by a whole step).
+  //
+  // Blocks that may reach the diagonal (masked steps) are settled when their scores exist: mask,
+  // true column maxima, reference raised if needed - so block j arrives settled and block j+1 is
+  // settled at the end of the step.
+  //
+  // Fully visible blocks (unmasked steps) take no maxima at all.  Their probabilities are formed
+  // against the reference as it stands and the block sums tell whether that was safe: a lane's sum
+  // of 16 probabilities above kSumGuard (or not finite) means some score outgrew the reference by
+  // more than the slack.  Only then (rare, wave-uniform) the block's scores are recomputed from
+  // the tile still in LDS, the reference is raised to their true maximum and the probabilities
+  // are redone; nothing has been accumulated from the discarded ones.
+  constexpr float kSumGuard = 4096.0f;   // 16 probabilities of at most 2^kRescaleSlack each
   auto step = [&](int buf_cur, int kb_cur, int buf_nxt, int kb_nxt, int key0_nxt, int buf_pre, int kb_pre,
-                  auto mask_next_tag) __attribute__((always_inline)) {
+                  auto masked_tag) __attribute__((always_inline)) {
+    constexpr bool kMasked = decltype(masked_tag)::value;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       s_cur[qb] = s_next[qb];
@@ -456,12 +487,31 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
         const typename T::frag k_now = kk < kKPre ? kf[kk < kKPre ? kk : 0] : T::load_k(kt, kb_nxt, kk);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) s_next[qb] = T::mma(k_now, qf[qb][kk], s_next[qb]);
+#if MC_KRING
+        // the register that fed this MFMA takes the same fragment of the block after next at once
+        if (kk < kKPre) kf[kk] = T::load_k(k_lane + buf_pre * kStageBytes, kb_pre, kk);
+#endif
       }
     }
+#if !MC_KRING
     load_k_block(buf_pre, kb_pre);
-    probabilities(s_cur);
-    pv_block(buf_cur, kb_cur, s_cur);
-    settle_reference(s_next, key0_nxt, mask_next_tag);
+#endif
+    float bsum[QB];
+    typename T::pblock pb[QB];
+    probabilities(s_cur, pb, bsum);
+    if (!kMasked) {
+      bool unsafe = false;
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) unsafe = unsafe || !(bsum[qb] <= kSumGuard);
+      if (__builtin_amdgcn_ballot_w64(unsafe) != 0) {
+        qk_block(buf_cur, kb_cur, s_cur);
+        settle_reference(s_cur, 0, std::false_type{});
+        probabilities(s_cur, pb, bsum);
+      }
+    }
+    add_sums(bsum);
+    pv_block(buf_cur, kb_cur, pb);
+    if (kMasked) settle_reference(s_next, key0_nxt, std::true_type{});
   };
 
   load_ids(0);
@@ -481,9 +531,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   int buf = 0;
   // One tile = barrier, enqueue the copy of tile + 2, two steps.  After the barrier tile + 1 is
   // visible to every wave (it was enqueued a whole tile ago) and no wave reads tile - 1 any
-  // more, so that buffer takes tile + 2.  mask_tag says whether the blocks SETTLED in this
-  // tile (its second block and the first block of the next tile) may reach the diagonal.
-  auto tile_body = [&](int tile, bool more, auto mask_tag) __attribute__((always_inline)) {
+  // more, so that buffer takes tile + 2.
+  auto tile_body = [&](int tile, bool more, auto masked_tag) __attribute__((always_inline)) {
     const int buf_next = buf == 2 ? 0 : buf + 1;
     copies_landed();
     __syncthreads();
@@ -493,20 +542,25 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
     }
     // block 0: scores of block 1 (same tile), prefetch K of the next tile's block 0
     // (on the last tile that buffer holds stale but in-bounds data nobody uses)
-    step(buf, 0, buf, 1, tile * kTileKeys + 32, buf_next, 0, mask_tag);
+    step(buf, 0, buf, 1, tile * kTileKeys + 32, buf_next, 0, masked_tag);
     if (more) {
       // block 1: scores of the next tile's block 0, prefetch K of its block 1
-      step(buf, 1, buf_next, 0, (tile + 1) * kTileKeys, buf_next, 1, mask_tag);
+      step(buf, 1, buf_next, 0, (tile + 1) * kTileKeys, buf_next, 1, masked_tag);
     } else {
-      probabilities(s_next);
-      pv_block(buf, 1, s_next);
+      float bsum[QB];
+      typename T::pblock pb[QB];
+      probabilities(s_next, pb, bsum);
+      add_sums(bsum);
+      pv_block(buf, 1, pb);
     }
     buf = buf_next;
   };
   int tile = 0;
-  // tiles whose own second block and whose successor's first block are fully visible
-  for (; tile < n_free - 1; ++tile) tile_body(tile, true, std::false_type{});
-  // the rest (the tiles on the chunk's diagonal, and one tile before them)
+  // tiles every key of which is visible to every row (never the last tile: it ends the pipeline)
+  const int n_plain = n_free < n_tiles - 1 ? n_free : n_tiles - 1;
+  for (; tile < n_plain; ++tile) tile_body(tile, true, std::false_type{});
+  // the rest reach the diagonal; their first block has not been settled by an unmasked step
+  if (tile > 0) settle_reference(s_next, tile * kTileKeys, std::true_type{});
   for (; tile < n_tiles; ++tile) tile_body(tile, tile + 1 < n_tiles, std::true_type{});
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) l_run[qb] = sum_with_other_half(l_sum[qb]);
