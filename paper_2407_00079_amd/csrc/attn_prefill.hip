@@ -5,7 +5,7 @@
 // Shape of the computation
 //   * A workgroup owns a tile of stacked query rows of one (request, KV head):
 //     row = token * G + head_in_group, so a K/V tile staged once in LDS feeds all
-//     G query heads that share the KV head.  Each wave takes QB blocks of 32 rows.
+//     G query heads that share the KV head.  Each wave takes one block of 32 rows.
 //   * Scores are computed TRANSPOSED, S^T = K Q^T, on 32x32 MFMA tiles.  In the
 //     accumulator a lane then owns ONE query column (lane % 32) and 16 keys per
 //     32-key block, so the softmax row reductions are in-lane plus one exchange
@@ -43,15 +43,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #ifndef MC_WAVES
 #define MC_WAVES 8
-#endif
-#ifndef MC_QB
-#define MC_QB 1
-#endif
-#ifndef MC_KRING
-#define MC_KRING 0
-#endif
-#ifndef MC_KPRE
-#define MC_KPRE 2
 #endif
 
 constexpr int kTileKeys = 64;          // keys per LDS tile = 4 pages of 16
@@ -145,6 +136,18 @@ struct Bf16 {
     return b;
   }
   static __device__ __forceinline__ frag p_frag(const pblock& b, int step) { return b.f[step]; }
+  // round probabilities e0, e0+1 into their fragment and add the ROUNDED values to acc (one
+  // v_cvt_pk_bf16_f32, one v_dot2c_f32_bf16)
+  template <int N>
+  static __device__ __forceinline__ float round_sum(pblock& b, const f32x16& p, int e0, float acc) {
+    static_assert(N == 2, "bf16 probabilities are rounded in pairs");
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    const bf16x2 pr = {(__bf16)p[e0], (__bf16)p[e0 + 1]};
+    b.f[e0 >> 3][e0 & 7] = pr[0];
+    b.f[e0 >> 3][(e0 & 7) + 1] = pr[1];
+    return __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
+  }
   // sum of the 16 ROUNDED probabilities, two per v_dot2c_f32_bf16 with fp32 accumulation
   static __device__ __forceinline__ float block_sum(const pblock& b) {
     typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
@@ -205,6 +208,12 @@ struct F32 {
   struct pblock { f32x16 p; };
   static __device__ __forceinline__ pblock round_p(const f32x16& p) { return pblock{p}; }
   static __device__ __forceinline__ frag p_frag(const pblock& b, int step) { return b.p[step]; }
+  template <int N>
+  static __device__ __forceinline__ float round_sum(pblock& b, const f32x16& p, int e0, float acc) {
+    static_assert(N == 1, "f32 probabilities are taken one at a time");
+    b.p[e0] = p[e0];
+    return acc + p[e0];
+  }
   static __device__ __forceinline__ float block_sum(const pblock& b) {
     float acc = 0.f;
 #pragma unroll
@@ -220,11 +229,11 @@ struct F32 {
 // ---------------------------------------------------------------------------
 // kernel
 // ---------------------------------------------------------------------------
-template <class T, int WAVES, int QB>
+template <class T, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) char smem[3 * kStageBytes];   // three (K, V) tiles
   constexpr int kThreads = WAVES * 64;
-  constexpr int kTileRows = WAVES * QB * 32;
+  constexpr int kTileRows = WAVES * 32;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -239,22 +248,17 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   const int n_rows = rq.chunk * G;
   const int last_page = rq.pages - 1;
 
-  // ---- this lane's query rows: Q fragments stay in registers for the whole KV loop
-  typename T::frag qf[QB][T::kQKSteps];
-  int tok[QB];      // token index inside the chunk
-  int qhead[QB];
-  bool live[QB];
+  // ---- this lane's query row: its Q fragments stay in registers for the whole KV loop
+  typename T::frag qf[T::kQKSteps];
+  int row = item.row0 + wave * 32 + (lane & 31);
+  const bool live = row < n_rows;
+  row = live ? row : n_rows - 1;                // dead rows recompute the last row, never stored
+  const int tok = row / G;                      // token index inside the chunk
+  const int qhead = item.kv_head * G + (row - tok * G);
+  {
+    const char* qrow = reinterpret_cast<const char*>(a.q) + ((int64_t)(rq.q_off + tok) * a.Hq + qhead) * kRowBytes;
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    int row = item.row0 + (wave * QB + qb) * 32 + (lane & 31);
-    live[qb] = row < n_rows;
-    row = live[qb] ? row : n_rows - 1;          // dead rows recompute the last row, never stored
-    tok[qb] = row / G;
-    qhead[qb] = item.kv_head * G + (row - tok[qb] * G);
-    const char* qrow = reinterpret_cast<const char*>(a.q) +
-                       ((int64_t)(rq.q_off + tok[qb]) * a.Hq + qhead[qb]) * kRowBytes;
-#pragma unroll
-    for (int kk = 0; kk < T::kQKSteps; ++kk) qf[qb][kk] = T::load_q(qrow, kk, half);
+    for (int kk = 0; kk < T::kQKSteps; ++kk) qf[kk] = T::load_q(qrow, kk, half);
   }
 
   // ---- keys this workgroup needs, and how many leading tiles need no mask
@@ -340,129 +344,103 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   auto copies_landed = [&]() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0x0F70); };
 
   // ---- running softmax state and output accumulators (O^T: registers index head_dim)
-  f32x16 o[QB][T::kDBlocks];
-  float m_run[QB], l_run[QB], l_sum[QB];   // l_sum: this lane's share of the row sum (halves merged at the end)
+  f32x16 o[T::kDBlocks];
+  float m_run = -INFINITY;   // reference of the probabilities accumulated so far (log2 units)
+  float l_sum = 0.f;         // this lane's share of the row sum (halves merged at the end)
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m_run[qb] = -INFINITY;
-    l_sum[qb] = 0.f;
+  for (int db = 0; db < T::kDBlocks; ++db)
 #pragma unroll
-    for (int db = 0; db < T::kDBlocks; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
-  }
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   const float c = a.scale_log2e;
   const uint32_t smem_base = (uint32_t)(uintptr_t)(MC_LDS char*)smem;
   const uint32_t k_lane = smem_base + T::k_lane_off(lane);
   const uint32_t v_lane = smem_base + kKTileBytes + T::v_lane_off(lane);
 
-  // ---- the three stages of one 32-key block
-  // S^T block = K Q^T for keys [32*kb, 32*kb+32) of the tile in LDS buffer `buf`
-  auto qk_block = [&](int buf, int kb, f32x16 (&s)[QB]) {
+  // ---- building blocks that are NOT on the steady-state path (prologue, last block, rare recompute)
+  // S^T block = K Q^T for keys [32*kb, 32*kb+32) of the tile in LDS buffer `buf`, one K fragment
+  // in flight at a time (it runs where registers are scarce)
+  auto qk_block = [&](int buf, int kb, f32x16& s) __attribute__((always_inline)) {
     const uint32_t kt = k_lane + buf * kStageBytes;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[qb][r] = 0.f;
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < T::kQKSteps; ++kk) {
       const typename T::frag kf = T::load_k(kt, kb, kk);
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) s[qb] = T::mma(kf, qf[qb][kk], s[qb]);
+      s = T::mma(kf, qf[kk], s);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // Softmax of one block is split in two so that neither part needs a branch next to MFMAs:
-  // (1) as soon as a block's scores exist: mask them if the block reaches the diagonal, take the
-  //     column maxima and raise the reference m_run if some column outgrew it by the slack
-  //     (rare, wave-uniform branch; always taken for the first block, m_run starts at -inf);
-  auto settle_reference = [&](f32x16 (&s)[QB], int key0, auto masked_tag) {
+  // Mask a block if it reaches the diagonal, take the TRUE column maxima and raise the reference
+  // m_run if some column outgrew it by more than the slack (rare, wave-uniform branch; always taken
+  // for the first block, m_run starts at -inf).
+  auto settle_reference = [&](f32x16& s, int key0, auto masked_tag) __attribute__((always_inline)) {
     constexpr bool kMasked = decltype(masked_tag)::value;
-    float mx[QB];
-    bool grow = false;
+    if (kMasked) {
+      // key of register r: key0 + 8*(r/4) + 4*half + r%4; visible iff <= P + tok
+      const int lim = P + tok - key0 - half * 4;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      if (kMasked) {
-        // key of register r: key0 + 8*(r/4) + 4*half + r%4; visible iff <= P + tok
-        const int lim = P + tok[qb] - key0 - half * 4;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[qb][r] = ((r >> 2) * 8 + (r & 3) <= lim) ? s[qb][r] : -INFINITY;
-      }
-      mx[qb] = s[qb][0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mx[qb] = fmaxf(mx[qb], s[qb][r]);
-      mx[qb] = max_with_other_half(mx[qb]) * c;
-      grow = grow || (mx[qb] > m_run[qb] + kRescaleSlack);
+      for (int r = 0; r < 16; ++r) s[r] = ((r >> 2) * 8 + (r & 3) <= lim) ? s[r] : -INFINITY;
     }
-    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+    float mx = s[0];
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const float m_new = fmaxf(m_run[qb], mx[qb]);
-        const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
-        l_sum[qb] *= alpha;
-        m_run[qb] = m_new;
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+    mx = max_with_other_half(mx) * c;
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      l_sum *= alpha;
+      m_run = m_new;
 #pragma unroll
-        for (int db = 0; db < T::kDBlocks; ++db)
+      for (int db = 0; db < T::kDBlocks; ++db)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
-      }
+        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
     }
   };
-  // (2) scores -> probabilities relative to the reference, in the form P V multiplies; straight-line
-  //     code.  bsum: this lane's share of each column's sum over the block.
-  auto probabilities = [&](const f32x16 (&s)[QB], typename T::pblock (&pb)[QB], float (&bsum)[QB]) {
+  // scores -> probabilities against the reference as it stands, rounded the way P V multiplies them;
+  // returns this lane's share of the block's column sums
+  auto probabilities = [&](const f32x16& s, typename T::pblock& pb) __attribute__((always_inline)) {
+    f32x16 p;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      const float m_ref = m_run[qb];
-      f32x16 p;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[qb][r], c, -m_ref));
-      pb[qb] = T::round_p(p);
-      bsum[qb] = T::block_sum(pb[qb]);
-    }
+    for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -m_run));
+    pb = T::round_p(p);
+    return T::block_sum(pb);
   };
-  auto add_sums = [&](const float (&bsum)[QB]) {
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) l_sum[qb] += bsum[qb];
-  };
-  // O^T += V^T P^T for the block's 32 keys
-  auto pv_block = [&](int buf, int kb, const typename T::pblock (&pb)[QB]) {
+  // O^T += V^T P^T for the block's 32 keys, V fragments read just in time
+  auto pv_block = [&](int buf, int kb, const typename T::pblock& pb) __attribute__((always_inline)) {
     const uint32_t vt = v_lane + buf * kStageBytes;
 #pragma unroll
-    for (int st = 0; st < T::kPVSteps; ++st) {
-      typename T::frag pf[QB];
+    for (int st = 0; st < T::kPVSteps; ++st)
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb) pf[qb] = T::p_frag(pb[qb], st);
-#pragma unroll
-      for (int db = 0; db < T::kDBlocks; ++db) {
-        const typename T::frag vf = T::load_v(vt, kb, st, db);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) o[qb][db] = T::mma(vf, pf[qb], o[qb][db]);
-      }
-    }
+      for (int db = 0; db < T::kDBlocks; ++db) o[db] = T::mma(T::load_v(vt, kb, st, db), T::p_frag(pb, st), o[db]);
   };
 
-  // ---- KV loop.  Software pipeline over 32-key blocks: one step turns the settled scores of
-  //      block j into probabilities and accumulates P V, while the score MFMAs of block j+1 are
-  //      in the same straight-line region, so the matrix pipe works under the vector ALU.
+  // ---- KV loop.  Software pipeline over 32-key blocks, scheduled by hand: the order written
+  //      below is the order issued (a scheduling barrier closes every group).
+  //
+  //      One step has two phases and one ring of kRing fragment registers:
+  //        phase A  scores of block j+1: MFMA i multiplies ring[i] (K fragment i of block j+1, read
+  //                 during the previous phase B) and frees it; the V fragment that P V step i of
+  //                 block j needs is read into the freed slot; under these MFMAs the vector ALU
+  //                 turns the scores of block j into probabilities, a group's share per MFMA.
+  //        phase B  P V of block j: MFMA i multiplies ring[i] (the V fragment) and frees it; K
+  //                 fragment i of block j+2 is read into the freed slot.
+  //      Every LDS read is thus issued about a phase (8 MFMAs) before its consumer.
   //      Tiles are triple buffered in LDS: the copy of tile t+2 is enqueued at the start of
   //      tile t (right after the one barrier per tile), into the buffer tile t-1 has just left.
-  f32x16 s_cur[QB], s_next[QB];
-  // The first kKPre K fragments of the block whose scores the NEXT step computes are fetched a
-  // step ahead; the rest are read at the start of that step, under its first MFMAs.
-  constexpr int kKPre = T::kQKSteps < MC_KPRE ? T::kQKSteps : MC_KPRE;
-  typename T::frag kf[kKPre];
-  auto load_k_block = [&](int buf, int kb) __attribute__((always_inline)) {
+  constexpr int kRing = T::kQKSteps;
+  static_assert(kRing == T::kPVSteps * T::kDBlocks, "both phases must have the same number of MFMAs");
+  constexpr int kPer = kRing >= 16 ? 1 : 16 / kRing;      // scores turned into probabilities per active group
+  constexpr int kEvery = kRing >= 16 ? kRing / 16 : 1;    // every kEvery-th group is active
+  typename T::frag ring[kRing];
+  f32x16 s_cur, s_next;
+  auto load_k_ring = [&](int buf, int kb) __attribute__((always_inline)) {
     const uint32_t kt = k_lane + buf * kStageBytes;
 #pragma unroll
-    for (int kk = 0; kk < kKPre; ++kk) kf[kk] = T::load_k(kt, kb, kk);
+    for (int i = 0; i < kRing; ++i) ring[i] = T::load_k(kt, kb, i);
   };
-  // One step: scores of block j+1 from the K fragments fetched during the previous step,
-  // probabilities and P V of block j, then the K fragments of block j+2 (their LDS latency
-  // is covered by a whole step).
-  //
-  // Blocks that may reach the diagonal (masked steps) are settled when their scores exist: mask,
-  // true column maxima, reference raised if needed - so block j arrives settled and block j+1 is
-  // settled at the end of the step.
+
+  // Blocks that may reach the diagonal (masked steps) are settled when their scores exist: block j
+  // arrives settled and block j+1 is settled at the end of the step.
   //
   // Fully visible blocks (unmasked steps) take no maxima at all.  Their probabilities are formed
   // against the reference as it stands and the block sums tell whether that was safe: a lane's sum
@@ -471,46 +449,48 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   // the tile still in LDS, the reference is raised to their true maximum and the probabilities
   // are redone; nothing has been accumulated from the discarded ones.
   constexpr float kSumGuard = 4096.0f;   // 16 probabilities of at most 2^kRescaleSlack each
-  auto step = [&](int buf_cur, int kb_cur, int buf_nxt, int kb_nxt, int key0_nxt, int buf_pre, int kb_pre,
+  // step(block j = (buf_cur, kb_cur); first key of block j+1; block j+2 = (buf_pre, kb_pre))
+  auto step = [&](int buf_cur, int kb_cur, int key0_nxt, int buf_pre, int kb_pre,
                   auto masked_tag) __attribute__((always_inline)) {
     constexpr bool kMasked = decltype(masked_tag)::value;
+    const uint32_t vt = v_lane + buf_cur * kStageBytes;
+    const uint32_t kt = k_lane + buf_pre * kStageBytes;
+    s_cur = s_next;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      s_cur[qb] = s_next[qb];
+    for (int r = 0; r < 16; ++r) s_next[r] = 0.f;
+    typename T::pblock pb;
+    float bsum = 0.f;
+    const float m_ref = m_run;
+    // ---- phase A
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s_next[qb][r] = 0.f;
-    }
-    {
-      const uint32_t kt = k_lane + buf_nxt * kStageBytes;
+    for (int i = 0; i < kRing; ++i) {
+      s_next = T::mma(ring[i], qf[i], s_next);
+      ring[i] = T::load_v(vt, kb_cur, i / T::kDBlocks, i % T::kDBlocks);
+      if (i % kEvery == 0) {
+        const int e0 = i / kEvery * kPer;
 #pragma unroll
-      for (int kk = 0; kk < T::kQKSteps; ++kk) {
-        const typename T::frag k_now = kk < kKPre ? kf[kk < kKPre ? kk : 0] : T::load_k(kt, kb_nxt, kk);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) s_next[qb] = T::mma(k_now, qf[qb][kk], s_next[qb]);
-#if MC_KRING
-        // the register that fed this MFMA takes the same fragment of the block after next at once
-        if (kk < kKPre) kf[kk] = T::load_k(k_lane + buf_pre * kStageBytes, kb_pre, kk);
-#endif
+        for (int e = e0; e < e0 + kPer; ++e) s_cur[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur[e], c, -m_ref));
+        // rounding and summing trail one group behind the exponentials they depend on
+        if (i > 0) bsum = T::template round_sum<kPer>(pb, s_cur, e0 - kPer, bsum);
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
-#if !MC_KRING
-    load_k_block(buf_pre, kb_pre);
-#endif
-    float bsum[QB];
-    typename T::pblock pb[QB];
-    probabilities(s_cur, pb, bsum);
+    bsum = T::template round_sum<kPer>(pb, s_cur, 16 - kPer, bsum);
     if (!kMasked) {
-      bool unsafe = false;
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) unsafe = unsafe || !(bsum[qb] <= kSumGuard);
-      if (__builtin_amdgcn_ballot_w64(unsafe) != 0) {
+      if (__builtin_amdgcn_ballot_w64(!(bsum <= kSumGuard)) != 0) {
         qk_block(buf_cur, kb_cur, s_cur);
         settle_reference(s_cur, 0, std::false_type{});
-        probabilities(s_cur, pb, bsum);
+        bsum = probabilities(s_cur, pb);
       }
     }
-    add_sums(bsum);
-    pv_block(buf_cur, kb_cur, pb);
+    l_sum += bsum;
+    // ---- phase B
+#pragma unroll
+    for (int i = 0; i < kRing; ++i) {
+      o[i % T::kDBlocks] = T::mma(ring[i], T::p_frag(pb, i / T::kDBlocks), o[i % T::kDBlocks]);
+      ring[i] = T::load_k(kt, kb_pre, i);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     if (kMasked) settle_reference(s_next, key0_nxt, std::true_type{});
   };
 
@@ -527,7 +507,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   __syncthreads();
   qk_block(0, 0, s_next);
   settle_reference(s_next, 0, std::true_type{});
-  load_k_block(0, 1);
+  load_k_ring(0, 1);
   int buf = 0;
   // One tile = barrier, enqueue the copy of tile + 2, two steps.  After the barrier tile + 1 is
   // visible to every wave (it was enqueued a whole tile ago) and no wave reads tile - 1 any
@@ -540,17 +520,15 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
       fetch(tile + 2, buf == 0 ? 2 : buf - 1);   // (tile + 2) % 3, ids loaded one tile ago
       load_ids(tile + 3);
     }
-    // block 0: scores of block 1 (same tile), prefetch K of the next tile's block 0
+    // block 0: scores of block 1 (same tile), then the K fragments of the next tile's block 0
     // (on the last tile that buffer holds stale but in-bounds data nobody uses)
-    step(buf, 0, buf, 1, tile * kTileKeys + 32, buf_next, 0, masked_tag);
+    step(buf, 0, tile * kTileKeys + 32, buf_next, 0, masked_tag);
     if (more) {
-      // block 1: scores of the next tile's block 0, prefetch K of its block 1
-      step(buf, 1, buf_next, 0, (tile + 1) * kTileKeys, buf_next, 1, masked_tag);
+      // block 1: scores of the next tile's block 0, then the K fragments of its block 1
+      step(buf, 1, (tile + 1) * kTileKeys, buf_next, 1, masked_tag);
     } else {
-      float bsum[QB];
-      typename T::pblock pb[QB];
-      probabilities(s_next, pb, bsum);
-      add_sums(bsum);
+      typename T::pblock pb;
+      l_sum += probabilities(s_next, pb);
       pv_block(buf, 1, pb);
     }
     buf = buf_next;
@@ -562,39 +540,35 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   // the rest reach the diagonal; their first block has not been settled by an unmasked step
   if (tile > 0) settle_reference(s_next, tile * kTileKeys, std::true_type{});
   for (; tile < n_tiles; ++tile) tile_body(tile, tile + 1 < n_tiles, std::true_type{});
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) l_run[qb] = sum_with_other_half(l_sum[qb]);
+  const float l_run = sum_with_other_half(l_sum);
 
   // ---- epilogue: normalise, round, store; lane holds 4 consecutive columns per (db, r/4)
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    if (!live[qb]) continue;
-    const float inv = 1.0f / l_run[qb];
-    const int64_t orow_idx = (int64_t)(rq.q_off + tok[qb]) * a.Hq + qhead[qb];
+  if (live) {
+    const float inv = 1.0f / l_run;
+    const int64_t orow_idx = (int64_t)(rq.q_off + tok) * a.Hq + qhead;
     char* orow = reinterpret_cast<char*>(a.out) + orow_idx * kRowBytes;
 #pragma unroll
     for (int db = 0; db < T::kDBlocks; ++db)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         const int col = db * 32 + q4 * 8 + half * 4;
-        T::store4(orow, col, o[qb][db][q4 * 4 + 0] * inv, o[qb][db][q4 * 4 + 1] * inv,
-                  o[qb][db][q4 * 4 + 2] * inv, o[qb][db][q4 * 4 + 3] * inv);
+        T::store4(orow, col, o[db][q4 * 4 + 0] * inv, o[db][q4 * 4 + 1] * inv, o[db][q4 * 4 + 2] * inv,
+                  o[db][q4 * 4 + 3] * inv);
       }
-    if (a.lse != nullptr && half == 0)
-      a.lse[orow_idx] = (m_run[qb] + __builtin_amdgcn_logf(l_run[qb])) * 0.6931471805599453f;
+    if (a.lse != nullptr && half == 0) a.lse[orow_idx] = (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f;
   }
 }
 
 }  // namespace
 
-int attn_tile_rows(int dtype) { return dtype == MC_DTYPE_BF16 ? MC_WAVES * MC_QB * 32 : MC_WAVES * 32; }
+int attn_tile_rows(int) { return MC_WAVES * 32; }
 
 hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream) {
   (void)hipGetLastError();   // drop any stale error of earlier, unrelated runtime calls
   if (dtype == MC_DTYPE_BF16)
-    attn_prefill_kernel<Bf16, MC_WAVES, MC_QB><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
+    attn_prefill_kernel<Bf16, MC_WAVES><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
   else
-    attn_prefill_kernel<F32, MC_WAVES, 1><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
+    attn_prefill_kernel<F32, MC_WAVES><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
   return hipGetLastError();
 }
 
