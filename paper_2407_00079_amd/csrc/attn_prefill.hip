@@ -74,6 +74,20 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
   return a + b;
 }
 
+// Direct global -> LDS copy of 16 bytes per lane: lane i's bytes land at lds_base + 16*i
+// (lds_base wave-uniform, it travels in M0).  Written as asm so that the compiler does not
+// know LDS is being written behind its back: it would otherwise make the first LDS read
+// after the copy wait for the copy (vmcnt), which is exactly what the tile pipeline avoids.
+// Ordering is the kernel's own business: s_waitcnt vmcnt(0) + barrier before a tile is read.
+__device__ __forceinline__ void dma16(const char* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
+               :: "s"(sbase), "v"(voff), "s"(lds_base) : "m0", "memory");
+}
+__device__ __forceinline__ void dma16(const char* vaddr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(vaddr), "s"(lds_base) : "m0", "memory");
+}
+
 // ---------------------------------------------------------------------------
 // dtype traits: how fragments are fetched and multiplied
 // ---------------------------------------------------------------------------
@@ -285,6 +299,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   const char* vbase = reinterpret_cast<const char*>(a.v_pool) + (int64_t)item.kv_head * kPageHeadBytes;
   const int64_t page_stride = (int64_t)a.Hkv * kPageHeadBytes;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const uint32_t smem_base = (uint32_t)(uintptr_t)(MC_LDS char*)smem;
   const bool fetcher = wave_u < kFetchWaves;
   // The block table is read through the scalar cache (it is constant while the kernel runs),
   // one tile AHEAD of the K/V loads that need it, so no wave ever waits for a page id.
@@ -293,14 +308,20 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   const int64_t first_page_off = (int64_t)btc[0] * page_stride;   // page of key 0: always valid
   int pid[kFetch];
 
+  int pid_next[kFetch];
+  // ids of tile `tile` into pid_next (issued before a barrier, so the scalar loads complete under it)
   auto load_ids = [&](int tile) __attribute__((always_inline)) {
     if (!fetcher) return;
 #pragma unroll
     for (int i = 0; i < kFetch; ++i) {
       int lp = tile * (kTileKeys / kPageTokens) + (wave_u + i * kFetchWaves) / 4;
       lp = lp < last_page ? lp : last_page;                  // never index the table past the request's pages
-      pid[i] = btc[lp];
+      pid_next[i] = btc[lp];
     }
+  };
+  auto take_ids = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < kFetch; ++i) pid[i] = pid_next[i];
   };
   // Per-lane byte offset inside a (page, head) block: the same for every chunk of a wave, because
   // a wave's chunks are 16 rows (one page) apart and both swizzles depend on row % 16 only.
@@ -311,17 +332,15 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   // enqueue the copy of tile `tile` (page ids in pid[]) into LDS buffer `buf`
   auto fetch = [&](int tile, int buf) __attribute__((always_inline)) {
     if (!fetcher) return;
-    char* dst0 = smem + buf * kStageBytes + wave_u * 1024;
+    const uint32_t dst0 = smem_base + buf * kStageBytes + wave_u * 1024;
     if ((tile + 1) * kTileKeys <= L) {
       // whole tile inside the sequence: scalar page base + constant lane offset
 #pragma unroll
       for (int i = 0; i < kFetch; ++i) {
         const int64_t page_off = (int64_t)pid[i] * page_stride;
-        char* dst = dst0 + i * kFetchWaves * 1024;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + page_off + k_src),
-                                         (MC_LDS void*)dst, 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + page_off + v_src),
-                                         (MC_LDS void*)(dst + kKTileBytes), 16, 0, 0);
+        const uint32_t dst = dst0 + i * kFetchWaves * 1024;
+        dma16(kbase + page_off, k_src, dst);
+        dma16(vbase + page_off, v_src, dst + kKTileBytes);
       }
     } else {
       // Slots at or past the request's length may hold anything (NaN would survive p = 0 in P V):
@@ -333,10 +352,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
         const int64_t page_off = (int64_t)pid[i] * page_stride;
         const char* ks = kbase + (in_seq ? page_off + k_src : first_page_off + (k_src & 255));
         const char* vs = vbase + (in_seq ? page_off + v_src : first_page_off + (v_src & 255));
-        char* dst = dst0 + i * kFetchWaves * 1024;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ks, (MC_LDS void*)dst, 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)vs,
-                                         (MC_LDS void*)(dst + kKTileBytes), 16, 0, 0);
+        const uint32_t dst = dst0 + i * kFetchWaves * 1024;
+        dma16(ks, dst);
+        dma16(vs, dst + kKTileBytes);
       }
     }
   };
@@ -352,7 +370,6 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   const float c = a.scale_log2e;
-  const uint32_t smem_base = (uint32_t)(uintptr_t)(MC_LDS char*)smem;
   const uint32_t k_lane = smem_base + T::k_lane_off(lane);
   const uint32_t v_lane = smem_base + kKTileBytes + T::v_lane_off(lane);
 
@@ -495,11 +512,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   };
 
   load_ids(0);
+  take_ids();
   fetch(0, 0);
   load_ids(1);
+  take_ids();
   if (n_tiles > 1) {
     fetch(1, 1);
     load_ids(2);
+    take_ids();
   }
   // everything issued so far has landed (Q fragments, tiles 0 and 1): inside the loop the
   // vector-memory counter only ever counts the tile copies
@@ -514,11 +534,13 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   // more, so that buffer takes tile + 2.
   auto tile_body = [&](int tile, bool more, auto masked_tag) __attribute__((always_inline)) {
     const int buf_next = buf == 2 ? 0 : buf + 1;
+    const bool ahead = tile + 2 < n_tiles;
+    if (ahead) load_ids(tile + 3);
     copies_landed();
     __syncthreads();
-    if (tile + 2 < n_tiles) {
+    if (ahead) {
       fetch(tile + 2, buf == 0 ? 2 : buf - 1);   // (tile + 2) % 3, ids loaded one tile ago
-      load_ids(tile + 3);
+      take_ids();
     }
     // block 0: scores of block 1 (same tile), then the K fragments of the next tile's block 0
     // (on the last tile that buffer holds stale but in-bounds data nobody uses)
