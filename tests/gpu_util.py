@@ -43,7 +43,10 @@ class DeviceCase:
         return self.out.float().cpu().numpy().astype(np.float64), self.lse.cpu().numpy().astype(np.float64)
 
 
-TOL = {W.BF16: dict(max_abs=2e-2, rel_l2=1e-2, lse_abs=2e-3),
+# lse (bf16): the row sum is taken over the probabilities as rounded to bf16 for P V.  Each rounded value is
+# off by at most 2^-8 relative (8 significant bits), so is their sum, so |delta lse| <= 2^-8 = 3.9e-3 nats; the
+# bound is met when one key dominates a row with a probability that bf16 does not represent.
+TOL = {W.BF16: dict(max_abs=2e-2, rel_l2=1e-2, lse_abs=4e-3),
        W.F32: dict(max_abs=1e-4, rel_l2=1e-5, lse_abs=1e-4)}
 
 
