@@ -40,6 +40,19 @@ def measured_traffic():
     return out
 
 
+def mfma_ceiling():
+    """Rate of back-to-back bf16 MFMAs alone on this board (zeros / ones / random operands), measured by the
+    stand-alone program built beside the library; None when it is missing or fails."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2407_00079_amd", "mfma_ceiling")
+    try:
+        out = subprocess.run([exe], capture_output=True, text=True, timeout=60, check=True).stdout.split()
+        return {out[i]: {"tflops": float(out[i + 1]), "shader_mhz": float(out[i + 2])} for i in (0, 3, 6)}
+    except Exception as e:      # measurement aid only: the benchmark goes on without it
+        sys.stderr.write(f"mfma_ceiling unavailable: {e}\n")
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -256,6 +269,15 @@ def main():
             del other
             torch.cuda.empty_cache()
 
+    if not args.no_extra:
+        torch.cuda.synchronize()
+        ceil = mfma_ceiling()
+        if ceil is not None:
+            result["mfma_alone"] = {
+                "what": "back-to-back bf16 32x32x16 MFMAs, nothing else running, 2 waves per SIMD, ~15 ms per case: "
+                        "the board lowers its clock to hold its power limit, and MFMA power follows operand bit activity",
+                **ceil,
+                "attn_vs_random_data_rate": round(result["roofline"]["achieved"] / ceil["random"]["tflops"], 4)}
     if args.cpu_rows > 0:
         # the CPU oracle, as it stands, on a bounded sample of the same attention workload
         import oracle

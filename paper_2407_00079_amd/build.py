@@ -11,6 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libmooncake_hip.so")
+PROBE = os.path.join(PKG, "mfma_ceiling")          # stand-alone measurement aid used by bench.py
 SOURCES = ["mc_api.hip", "attn_prefill.hip", "kv_copy.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -40,6 +41,11 @@ def build(extra_flags=(), verbose: bool = False) -> str:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.run(cmd, check=True)
+    res = subprocess.run([HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                          "-packed-fp32-ops", "-o", PROBE, os.path.join(CSRC, "mfma_ceiling.hip")],
+                         capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed on mfma_ceiling.hip:\n{res.stderr}")
     if verbose:
         print("built", LIB)
     return LIB
