@@ -52,6 +52,8 @@ def _load():
             f.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, i32]
         lib.mco_kv_append_paged.restype = ctypes.c_int
         lib.mco_kv_append_paged.argtypes = [vp, vp, vp, vp, i64, vp, i32, vp, vp, i32, i32, i32, i64]
+        lib.mco_attn_merge_lse.restype = ctypes.c_int
+        lib.mco_attn_merge_lse.argtypes = [vp, vp, i32, i64, i32, vp, vp]
         _lib = lib
     return _lib
 
@@ -190,3 +192,23 @@ def kv_append_paged(k_new: np.ndarray, v_new: np.ndarray, k_pool: np.ndarray, v_
                                  _ptr(pl), _ptr(nl), pl.shape[0], Hkv, S, D * k_pool.itemsize)
     if rc != 0:
         raise ValueError("oracle rejected its arguments")
+
+
+def attn_merge_lse(o_parts: np.ndarray, lse_parts: np.ndarray):
+    """Merge partial attention results over disjoint key subsets.
+
+    ``o_parts`` [n_parts, rows, D] and ``lse_parts`` [n_parts, rows] are float32 (the form the
+    partials are stored in); returns (out [rows, D] f64, lse [rows] f64).
+    """
+    lib = _load()
+    assert o_parts.dtype == np.float32 and lse_parts.dtype == np.float32
+    o_parts = np.ascontiguousarray(o_parts)
+    lse_parts = np.ascontiguousarray(lse_parts)
+    n_parts, rows, D = o_parts.shape
+    assert lse_parts.shape == (n_parts, rows)
+    out = np.zeros((rows, D), dtype=np.float64)
+    lse = np.zeros(rows, dtype=np.float64)
+    rc = lib.mco_attn_merge_lse(_ptr(o_parts), _ptr(lse_parts), n_parts, rows, D, _ptr(out), _ptr(lse))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return out, lse

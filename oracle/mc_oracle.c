@@ -268,3 +268,39 @@ int mco_kv_append_paged(const uint8_t* k_new, const uint8_t* v_new, uint8_t* k_p
     }
   return 0;
 }
+
+/*
+ * Merge of partial attention results over disjoint key subsets (Section 5.1: sequence
+ * parallelism rests on the attention operator being associative over slices of the keys).
+ * Part s holds, for every row, the softmax-weighted V sum over ITS keys, o_parts[s][row][:],
+ * and the log of its exponential sum, lse_parts[s][row] (natural log; -inf = the part saw no
+ * key of that row).  The whole row is
+ *     lse = log sum_s exp(lse_s),   out = sum_s exp(lse_s - lse) * o_s,
+ * written out as that definition with the usual shift by the largest lse_s.  A row none of
+ * whose parts saw a key gives out = 0, lse = -inf.  Partials are fp32, results fp64.
+ */
+int mco_attn_merge_lse(const float* o_parts, const float* lse_parts, int n_parts, int64_t rows, int D,
+                       double* out, double* lse) {
+  if (n_parts < 0 || rows < 0 || D < 0) return -1;
+  for (int64_t t = 0; t < rows; ++t) {
+    double m = -INFINITY;
+    for (int s = 0; s < n_parts; ++s) {
+      const double l = (double)lse_parts[(int64_t)s * rows + t];
+      if (l > m) m = l;
+    }
+    for (int d = 0; d < D; ++d) out[t * D + d] = 0.0;
+    if (m == -INFINITY) {
+      lse[t] = -INFINITY;
+      continue;
+    }
+    double Z = 0.0;
+    for (int s = 0; s < n_parts; ++s) Z += exp((double)lse_parts[(int64_t)s * rows + t] - m);
+    for (int s = 0; s < n_parts; ++s) {
+      const double w = exp((double)lse_parts[(int64_t)s * rows + t] - m) / Z;
+      if (w == 0.0) continue;   /* a part without keys may hold anything, NaN included */
+      for (int d = 0; d < D; ++d) out[t * D + d] += w * (double)o_parts[((int64_t)s * rows + t) * D + d];
+    }
+    lse[t] = m + log(Z);
+  }
+  return 0;
+}

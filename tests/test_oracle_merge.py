@@ -1,0 +1,105 @@
+"""Pins for the CPU oracle's merge of partial attention results (Section 5.1: the attention operator is
+associative over slices of the keys, which sequence-parallel prefill relies on)."""
+import numpy as np
+import pytest
+
+from paper_2407_00079_amd import workloads as W
+
+
+def slice_bounds(L, kv_splits, tile=64):
+    """Key range of every slice: whole 64-key tiles, ceil(tiles / kv_splits) per slice, the tail slices may be empty."""
+    tiles = -(-L // tile)
+    per = -(-tiles // kv_splits)
+    return [(min(s * per * tile, L), min((s + 1) * per * tile, L)) for s in range(kv_splits)]
+
+
+def all_rows(case):
+    return np.array([(r, h, i) for r in range(case.batch) for i in range(int(case.new_lens[r]))
+                     for h in range(case.num_q_heads)], dtype=np.int32)
+
+
+def oracle_partials(oracle, case, kv_splits):
+    """Partials over the key slices of every request, from the oracle's own range-restricted rows (fp64 -> fp32)."""
+    rows = all_rows(case)
+    n = rows.shape[0]
+    o = np.zeros((kv_splits, n, case.head_dim), dtype=np.float32)
+    l = np.zeros((kv_splits, n), dtype=np.float32)
+    for s in range(kv_splits):
+        lo = np.empty(n, dtype=np.int64)
+        hi = np.empty(n, dtype=np.int64)
+        for r in range(case.batch):
+            b = slice_bounds(int(case.prefix_lens[r] + case.new_lens[r]), kv_splits)[s]
+            sel = rows[:, 0] == r
+            lo[sel], hi[sel] = b
+        oo, ll, _ = oracle.case_rows(case, rows, key_lo=lo, key_hi=hi)
+        o[s], l[s] = oo, ll
+    return rows, o, l
+
+
+@pytest.mark.parametrize("kv_splits", [1, 2, 3, 8])
+def test_merged_slices_equal_the_whole(oracle, kv_splits):
+    # request 1 is shorter than kv_splits tiles for 8 slices: its tail slices are empty (lse = -inf)
+    case = W.make_attn_case(51, W.BF16, 4, 2, 128, 16, [200, 10], [75, 33], 64)
+    rows, o, l = oracle_partials(oracle, case, kv_splits)
+    if kv_splits == 8:
+        assert np.isinf(l).any()
+    out, lse = oracle.attn_merge_lse(o, l)
+    whole, whole_lse, _ = oracle.case_rows(case, rows)
+    # the partials went through fp32: 2^-24 relative on weights and values
+    np.testing.assert_allclose(out, whole, atol=2e-6)
+    np.testing.assert_allclose(lse, whole_lse, atol=2e-6)
+
+
+def test_merge_closed_forms(oracle):
+    rng = np.random.default_rng(5)
+    o = rng.standard_normal((1, 7, 16)).astype(np.float32)
+    l = rng.standard_normal((1, 7)).astype(np.float32)
+    # a single part is returned as it is
+    out, lse = oracle.attn_merge_lse(o, l)
+    np.testing.assert_array_equal(out, o[0].astype(np.float64))
+    np.testing.assert_array_equal(lse, l[0].astype(np.float64))
+    # two copies of one part: same mean, twice the mass
+    out2, lse2 = oracle.attn_merge_lse(np.concatenate([o, o]), np.concatenate([l, l]))
+    np.testing.assert_allclose(out2, o[0], rtol=1e-15)
+    np.testing.assert_allclose(lse2, l[0].astype(np.float64) + np.log(2.0), rtol=1e-15)
+    # two parts with weights 1 : 3 (lse differs by ln 3): out = (a + 3 b) / 4
+    a = rng.standard_normal((1, 7, 16)).astype(np.float32)
+    b = rng.standard_normal((1, 7, 16)).astype(np.float32)
+    la = np.zeros((1, 7), dtype=np.float32)
+    lb = np.full((1, 7), np.float32(np.log(3.0)))
+    out3, lse3 = oracle.attn_merge_lse(np.concatenate([a, b]), np.concatenate([la, lb]))
+    w = np.exp(np.float64(lb[0, 0]))
+    np.testing.assert_allclose(out3, (a[0] + w * b[0].astype(np.float64)) / (1 + w), rtol=1e-14, atol=1e-15)
+    np.testing.assert_allclose(lse3, np.log1p(w), rtol=1e-14)
+
+
+def test_merge_ignores_empty_parts_and_their_contents(oracle):
+    rng = np.random.default_rng(6)
+    o = rng.standard_normal((3, 5, 8)).astype(np.float32)
+    l = rng.standard_normal((3, 5)).astype(np.float32)
+    l[1] = -np.inf
+    o[1] = np.nan                                  # an empty part may hold anything
+    out, lse = oracle.attn_merge_lse(o, l)
+    ref, ref_lse = oracle.attn_merge_lse(o[[0, 2]], l[[0, 2]])
+    np.testing.assert_array_equal(out, ref)
+    np.testing.assert_array_equal(lse, ref_lse)
+    l[:] = -np.inf                                 # no part saw a key
+    out, lse = oracle.attn_merge_lse(o, l)
+    assert (out == 0).all() and np.isneginf(lse).all()
+
+
+def test_merge_is_order_free_and_associative(oracle):
+    rng = np.random.default_rng(7)
+    o = rng.standard_normal((4, 9, 8)).astype(np.float32)
+    l = (5 * rng.standard_normal((4, 9))).astype(np.float32)
+    out, lse = oracle.attn_merge_lse(o, l)
+    perm = [2, 0, 3, 1]
+    outp, lsep = oracle.attn_merge_lse(o[perm], l[perm])
+    np.testing.assert_allclose(outp, out, rtol=1e-14, atol=1e-15)
+    np.testing.assert_allclose(lsep, lse, rtol=1e-14)
+    # merge two and two, then the two results (through fp32, as the stored form demands)
+    o01, l01 = oracle.attn_merge_lse(o[:2], l[:2])
+    o23, l23 = oracle.attn_merge_lse(o[2:], l[2:])
+    outn, lsen = oracle.attn_merge_lse(np.stack([o01, o23]).astype(np.float32), np.stack([l01, l23]).astype(np.float32))
+    np.testing.assert_allclose(outn, out, atol=5e-6)
+    np.testing.assert_allclose(lsen, lse, atol=5e-6)
