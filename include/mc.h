@@ -106,6 +106,56 @@ mc_status mc_prefill_attn_paged(const mc_attn_params* p, const void* q, const vo
                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Split form of mc_prefill_attn_paged for chunks too small to fill the GPU against a long
+ * prefix, and the single exchange step of sequence-parallel prefill (Section 5.1: the attention
+ * operator is associative over slices of the keys).
+ *
+ * The keys of request r are cut into kv_splits slices of whole 64-key tiles,
+ * T_r = ceil(ceil((P_r + C_r) / 64) / kv_splits) tiles each: slice s covers keys
+ * [64 s T_r, min(64 (s + 1) T_r, P_r + C_r)); trailing slices may be empty.  For every slice s
+ * and output row (i, h) the call writes the PARTIAL result over the keys of the slice that the
+ * row may see:
+ *
+ *   o_parts[s][i][h][:]  fp32  softmax-weighted V sum over those keys (0 if there are none)
+ *   lse_parts[s][i][h]   fp32  natural log of their exponential sum    (-inf if there are none)
+ *
+ *   o_parts    dev  [kv_splits, total_new_tokens, Hq, D] fp32, 16-byte aligned
+ *   lse_parts  dev  [kv_splits, total_new_tokens, Hq]    fp32
+ *   workspace  dev  >= mc_prefill_attn_split_workspace_bytes(...)
+ *
+ * Everything else as mc_prefill_attn_paged.  kv_splits outside [1, MC_MAX_KV_SPLITS] is
+ * MC_ERR_SHAPE.  mc_attn_merge_lse turns the partials into the whole-row result.
+ */
+#define MC_MAX_KV_SPLITS 256
+size_t mc_prefill_attn_split_workspace_bytes(const mc_attn_params* p, int32_t batch,
+                                             int64_t total_new_tokens, int32_t kv_splits);
+mc_status mc_prefill_attn_paged_split(const mc_attn_params* p, const void* q, const void* k_pool,
+                                      const void* v_pool, const int32_t* block_tables,
+                                      int32_t max_pages_per_req, const int32_t* prefix_lens,
+                                      const int32_t* new_lens, int32_t batch, int32_t kv_splits,
+                                      float* o_parts, float* lse_parts, void* workspace,
+                                      size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Merge of partial attention results over disjoint key subsets (Section 5.1), whoever produced
+ * them (mc_prefill_attn_paged_split, or other GPUs holding other slices of the sequence):
+ *
+ *   lse[t]    = log sum_s exp(lse_parts[s][t])
+ *   out[t][:] = sum_s exp(lse_parts[s][t] - lse[t]) * o_parts[s][t][:]
+ *
+ *   o_parts    dev  [kv_splits, rows, head_dim] fp32
+ *   lse_parts  dev  [kv_splits, rows] fp32; -inf marks a part without keys: weight 0, its
+ *                   o_parts row is not read
+ *   out        dev  [rows, head_dim] of `dtype` (bf16: rounded to nearest even)
+ *   lse        dev  [rows] fp32, or NULL
+ *
+ * A row whose parts are all -inf gives out = 0, lse = -inf.  (head_dim, dtype) must be
+ * (128, MC_DTYPE_BF16) or (64, MC_DTYPE_F32).  rows == 0 is MC_OK and enqueues nothing.
+ */
+mc_status mc_attn_merge_lse(const float* o_parts, const float* lse_parts, int32_t kv_splits, int64_t rows,
+                            int32_t head_dim, int32_t dtype, void* out, float* lse, void* hip_stream);
+
+/*
  * Bytes of device workspace mc_kv_append_paged needs (the per-request table).  0 for batch < 0.
  */
 size_t mc_kv_append_workspace_bytes(int32_t batch);

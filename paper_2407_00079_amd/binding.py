@@ -19,7 +19,9 @@ MC_ERR_NULL, MC_ERR_SHAPE, MC_ERR_UNSUPPORTED, MC_ERR_ALIGN, MC_ERR_RANGE, MC_ER
 MC_DTYPE_BF16, MC_DTYPE_F32 = 0, 1
 
 EXPORTS = ("mc_status_string", "mc_prefill_attn_workspace_bytes", "mc_prefill_attn_paged",
-           "mc_kv_pack_layer", "mc_kv_unpack_layer", "mc_kv_append_workspace_bytes", "mc_kv_append_paged")
+           "mc_kv_pack_layer", "mc_kv_unpack_layer", "mc_kv_append_workspace_bytes", "mc_kv_append_paged",
+           "mc_prefill_attn_split_workspace_bytes", "mc_prefill_attn_paged_split", "mc_attn_merge_lse")
+MC_MAX_KV_SPLITS = 256
 
 
 class McAttnParams(ctypes.Structure):
@@ -65,6 +67,13 @@ def lib():
         l.mc_kv_append_paged.restype = ctypes.c_int
         l.mc_kv_append_paged.argtypes = [ctypes.POINTER(McAttnParams), vp, vp, vp, vp, vp, i32, vp, vp, i32, vp,
                                          ctypes.c_size_t, vp]
+        l.mc_prefill_attn_split_workspace_bytes.restype = ctypes.c_size_t
+        l.mc_prefill_attn_split_workspace_bytes.argtypes = [ctypes.POINTER(McAttnParams), i32, i64, i32]
+        l.mc_prefill_attn_paged_split.restype = ctypes.c_int
+        l.mc_prefill_attn_paged_split.argtypes = [ctypes.POINTER(McAttnParams), vp, vp, vp, vp, i32, vp, vp, i32, i32,
+                                                  vp, vp, vp, ctypes.c_size_t, vp]
+        l.mc_attn_merge_lse.restype = ctypes.c_int
+        l.mc_attn_merge_lse.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp]
         _lib = l
     return _lib
 
@@ -115,6 +124,48 @@ def mc_prefill_attn_paged(params: McAttnParams, q, k_pool, v_pool, block_tables,
                                    _stream_handle(stream))
     if st != MC_OK:
         raise McError(st, "mc_prefill_attn_paged")
+
+
+def mc_prefill_attn_split_workspace_bytes(params: McAttnParams, batch: int, total_new_tokens: int,
+                                          kv_splits: int) -> int:
+    return int(lib().mc_prefill_attn_split_workspace_bytes(ctypes.byref(params), batch, total_new_tokens, kv_splits))
+
+
+def mc_prefill_attn_paged_split_raw(params, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens,
+                                    batch, kv_splits, o_parts, lse_parts, workspace, workspace_bytes, hip_stream) -> int:
+    return int(lib().mc_prefill_attn_paged_split(ctypes.byref(params) if params is not None else None, q, k_pool,
+                                                 v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens, batch,
+                                                 kv_splits, o_parts, lse_parts, workspace, workspace_bytes, hip_stream))
+
+
+def mc_prefill_attn_paged_split(params: McAttnParams, q, k_pool, v_pool, block_tables, prefix_lens, new_lens,
+                                kv_splits: int, o_parts, lse_parts, workspace, stream=None) -> None:
+    """Enqueue attention over ``kv_splits`` key slices; partial results go to the fp32 device tensors
+    ``o_parts`` [kv_splits, total_new, Hq, D] and ``lse_parts`` [kv_splits, total_new, Hq]."""
+    batch = len(prefix_lens)
+    pl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in prefix_lens])
+    nl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in new_lens])
+    max_pages = int(block_tables.shape[1]) if block_tables is not None and block_tables.dim() == 2 else 0
+    ws_bytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    st = mc_prefill_attn_paged_split_raw(params, _dev_ptr(q), _dev_ptr(k_pool), _dev_ptr(v_pool),
+                                         _dev_ptr(block_tables), max_pages, ctypes.cast(pl, ctypes.c_void_p),
+                                         ctypes.cast(nl, ctypes.c_void_p), batch, kv_splits, _dev_ptr(o_parts),
+                                         _dev_ptr(lse_parts), _dev_ptr(workspace), ws_bytes, _stream_handle(stream))
+    if st != MC_OK:
+        raise McError(st, "mc_prefill_attn_paged_split")
+
+
+def mc_attn_merge_lse_raw(o_parts, lse_parts, kv_splits, rows, head_dim, dtype, out, lse, hip_stream) -> int:
+    return int(lib().mc_attn_merge_lse(o_parts, lse_parts, kv_splits, rows, head_dim, dtype, out, lse, hip_stream))
+
+
+def mc_attn_merge_lse(o_parts, lse_parts, kv_splits: int, rows: int, head_dim: int, dtype: int, out, lse=None,
+                      stream=None) -> None:
+    """Enqueue the merge of ``kv_splits`` partial results (fp32 device tensors) into ``out`` / ``lse``."""
+    st = mc_attn_merge_lse_raw(_dev_ptr(o_parts), _dev_ptr(lse_parts), kv_splits, rows, head_dim, dtype,
+                               _dev_ptr(out), _dev_ptr(lse), _stream_handle(stream))
+    if st != MC_OK:
+        raise McError(st, "mc_attn_merge_lse")
 
 
 def mc_kv_pack_layer_raw(k_pool, v_pool, num_pages, page_bytes, page_ids, n, k_out, v_out, hip_stream) -> int:

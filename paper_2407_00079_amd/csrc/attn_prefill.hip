@@ -53,6 +53,9 @@ constexpr int kKTileBytes = kTileKeys * kRowBytes;        // 16 KiB; rows dense,
 constexpr int kVTileBytes = kTileKeys * kRowBytes;
 constexpr int kStageBytes = kKTileBytes + kVTileBytes;    // a multiple of 32 KiB: XOR constants (< 256) never touch it
 constexpr float kRescaleSlack = 8.0f;  // log2 units the running max may lag behind
+// stands in for a reference of -inf when probabilities are formed: masked scores (-inf) then give
+// exp2(-inf) = 0 instead of exp2(-inf + inf) = NaN; a row with a finite score has a finite reference
+constexpr float kNoKeyYet = -1e30f;
 
 // Combine a value with the one held by lane ^ 32.  v_permlane32_swap exchanges the upper
 // half of its first register with the lower half of its second, so after it every lane
@@ -243,7 +246,11 @@ struct F32 {
 // ---------------------------------------------------------------------------
 // kernel
 // ---------------------------------------------------------------------------
-template <class T, int WAVES>
+// SPLIT: the work item covers only slice item.slice of the request's keys (whole 64-key tiles,
+// ceil(tiles / kv_splits) per slice) and writes a PARTIAL result - the normalised fp32 output
+// over its keys and their log-sum-exp (-inf where the slice holds no key the row may see) - for
+// mc_attn_merge_lse to combine (paper Section 5.1: attention is associative over key slices).
+template <class T, int WAVES, bool SPLIT>
 __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) char smem[3 * kStageBytes];   // three (K, V) tiles
   constexpr int kThreads = WAVES * 64;
@@ -280,9 +287,30 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   int tok_last = (item.row0 + kTileRows - 1) / G;
   tok_last = tok_last < rq.chunk - 1 ? tok_last : rq.chunk - 1;
   const int kv_end = P + tok_last + 1;                       // <= L
-  const int n_tiles = (kv_end + kTileKeys - 1) / kTileKeys;
+  int n_tiles = (kv_end + kTileKeys - 1) / kTileKeys;        // tiles [t_lo, n_tiles) are this item's
+  int t_lo = 0;
+  if (SPLIT) {
+    const int per = ((L + kTileKeys - 1) / kTileKeys + a.kv_splits - 1) / a.kv_splits;
+    t_lo = item.slice * per;
+    n_tiles = n_tiles < t_lo + per ? n_tiles : t_lo + per;
+  }
   int n_free = (P + tok_first + 1) / kTileKeys;              // every key of these tiles is visible to every row
   n_free = n_free < n_tiles ? n_free : n_tiles;
+  // where this lane's row goes: the output itself, or this slice's plane of the partials
+  const int64_t orow_idx = (int64_t)(rq.q_off + tok) * a.Hq + qhead;
+  if (SPLIT && t_lo >= n_tiles) {
+    // no key of the slice is visible to any row of the tile
+    if (live) {
+      char* orow = reinterpret_cast<char*>(a.o_parts) + ((int64_t)item.slice * a.rows_total + orow_idx) * (T::kD * 4);
+#pragma unroll
+      for (int db = 0; db < T::kDBlocks; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+          *reinterpret_cast<f32x4*>(orow + (db * 32 + q4 * 8 + half * 4) * 4) = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (half == 0) a.lse_parts[(int64_t)item.slice * a.rows_total + orow_idx] = -INFINITY;
+    }
+    return;
+  }
 
   // ---- global -> LDS, no registers in between.  One wave instruction writes 1 KiB of LDS (lane i
   //      its 16 bytes at +16*i): 4 tile rows x 16 granules, all inside one page.  Lane i fetches,
@@ -404,7 +432,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
     mx = max_with_other_half(mx) * c;
     if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleSlack) != 0) {
       const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      // a row that has seen no key yet keeps m_run = -inf (possible only in a slice that starts
+      // beyond the row's diagonal): nothing to rescale, and -inf - -inf must not reach exp2
+      const float alpha = (SPLIT && m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
       l_sum *= alpha;
       m_run = m_new;
 #pragma unroll
@@ -417,8 +447,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   // returns this lane's share of the block's column sums
   auto probabilities = [&](const f32x16& s, typename T::pblock& pb) __attribute__((always_inline)) {
     f32x16 p;
+    const float m_ref = SPLIT ? fmaxf(m_run, kNoKeyYet) : m_run;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -m_run));
+    for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], c, -m_ref));
     pb = T::round_p(p);
     return T::block_sum(pb);
   };
@@ -477,7 +508,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
     for (int r = 0; r < 16; ++r) s_next[r] = 0.f;
     typename T::pblock pb;
     float bsum = 0.f;
-    const float m_ref = m_run;
+    const float m_ref = SPLIT ? fmaxf(m_run, kNoKeyYet) : m_run;
     // ---- phase A
 #pragma unroll
     for (int i = 0; i < kRing; ++i) {
@@ -511,14 +542,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
     if (kMasked) settle_reference(s_next, key0_nxt, std::true_type{});
   };
 
-  load_ids(0);
+  load_ids(t_lo);
   take_ids();
-  fetch(0, 0);
-  load_ids(1);
+  fetch(t_lo, 0);
+  load_ids(t_lo + 1);
   take_ids();
-  if (n_tiles > 1) {
-    fetch(1, 1);
-    load_ids(2);
+  if (n_tiles > t_lo + 1) {
+    fetch(t_lo + 1, 1);
+    load_ids(t_lo + 2);
     take_ids();
   }
   // everything issued so far has landed (Q fragments, tiles 0 and 1): inside the loop the
@@ -526,7 +557,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   qk_block(0, 0, s_next);
-  settle_reference(s_next, 0, std::true_type{});
+  settle_reference(s_next, t_lo * kTileKeys, std::true_type{});
   load_k_ring(0, 1);
   int buf = 0;
   // One tile = barrier, enqueue the copy of tile + 2, two steps.  After the barrier tile + 1 is
@@ -555,19 +586,18 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
     }
     buf = buf_next;
   };
-  int tile = 0;
+  int tile = t_lo;
   // tiles every key of which is visible to every row (never the last tile: it ends the pipeline)
   const int n_plain = n_free < n_tiles - 1 ? n_free : n_tiles - 1;
   for (; tile < n_plain; ++tile) tile_body(tile, true, std::false_type{});
   // the rest reach the diagonal; their first block has not been settled by an unmasked step
-  if (tile > 0) settle_reference(s_next, tile * kTileKeys, std::true_type{});
+  if (tile > t_lo) settle_reference(s_next, tile * kTileKeys, std::true_type{});
   for (; tile < n_tiles; ++tile) tile_body(tile, tile + 1 < n_tiles, std::true_type{});
   const float l_run = sum_with_other_half(l_sum);
 
   // ---- epilogue: normalise, round, store; lane holds 4 consecutive columns per (db, r/4)
-  if (live) {
+  if (live && !SPLIT) {
     const float inv = 1.0f / l_run;
-    const int64_t orow_idx = (int64_t)(rq.q_off + tok) * a.Hq + qhead;
     char* orow = reinterpret_cast<char*>(a.out) + orow_idx * kRowBytes;
 #pragma unroll
     for (int db = 0; db < T::kDBlocks; ++db)
@@ -579,6 +609,54 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
       }
     if (a.lse != nullptr && half == 0) a.lse[orow_idx] = (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f;
   }
+  if (live && SPLIT) {
+    // partial result in fp32; a row that saw no key of the slice has l = 0: zeros and -inf
+    const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
+    char* orow = reinterpret_cast<char*>(a.o_parts) + ((int64_t)item.slice * a.rows_total + orow_idx) * (T::kD * 4);
+#pragma unroll
+    for (int db = 0; db < T::kDBlocks; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
+        *reinterpret_cast<f32x4*>(orow + (db * 32 + q4 * 8 + half * 4) * 4) =
+            f32x4{o[db][q4 * 4 + 0] * inv, o[db][q4 * 4 + 1] * inv, o[db][q4 * 4 + 2] * inv, o[db][q4 * 4 + 3] * inv};
+    if (half == 0)
+      a.lse_parts[(int64_t)item.slice * a.rows_total + orow_idx] =
+          l_run > 0.f ? (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f : -INFINITY;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// merge of partial results (paper Section 5.1: attention is associative over key slices):
+//   lse = log sum_s exp(lse_s),  out = sum_s exp(lse_s - lse) o_s
+// One thread owns 4 consecutive columns of one row and walks the parts; a part whose lse is -inf
+// has weight 0 and is not read.  D / 4 threads per row, rows packed into 256-thread workgroups.
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ o_parts,
+                                                         const float* __restrict__ lse_parts, int kv_splits,
+                                                         int64_t rows, void* __restrict__ out,
+                                                         float* __restrict__ lse) {
+  constexpr int kThreadsPerRow = T::kD / 4;
+  const int64_t row = (int64_t)blockIdx.x * (256 / kThreadsPerRow) + threadIdx.x / kThreadsPerRow;
+  const int col = (threadIdx.x % kThreadsPerRow) * 4;
+  if (row >= rows) return;
+  float m = -INFINITY;
+  for (int s = 0; s < kv_splits; ++s) m = fmaxf(m, lse_parts[(int64_t)s * rows + row]);
+  float z = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  if (m != -INFINITY) {
+    for (int s = 0; s < kv_splits; ++s) {
+      const float w = __expf(lse_parts[(int64_t)s * rows + row] - m);
+      if (w == 0.f) continue;
+      z += w;
+      const f32x4 v = *reinterpret_cast<const f32x4*>(o_parts + ((int64_t)s * rows + row) * T::kD + col);
+      acc += w * v;
+    }
+    const float inv = 1.0f / z;
+    acc *= inv;
+  }
+  T::store4(reinterpret_cast<char*>(out) + row * kRowBytes, col, acc[0], acc[1], acc[2], acc[3]);
+  if (lse != nullptr && col == 0) lse[row] = m != -INFINITY ? m + __logf(z) : -INFINITY;
 }
 
 }  // namespace
@@ -587,10 +665,27 @@ int attn_tile_rows(int) { return MC_WAVES * 32; }
 
 hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream) {
   (void)hipGetLastError();   // drop any stale error of earlier, unrelated runtime calls
-  if (dtype == MC_DTYPE_BF16)
-    attn_prefill_kernel<Bf16, MC_WAVES><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
-  else
-    attn_prefill_kernel<F32, MC_WAVES><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
+  const bool split = args.kv_splits > 0;
+  if (dtype == MC_DTYPE_BF16) {
+    if (split) attn_prefill_kernel<Bf16, MC_WAVES, true><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
+    else attn_prefill_kernel<Bf16, MC_WAVES, false><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
+  } else {
+    if (split) attn_prefill_kernel<F32, MC_WAVES, true><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
+    else attn_prefill_kernel<F32, MC_WAVES, false><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_merge(int dtype, const float* o_parts, const float* lse_parts, int kv_splits, int64_t rows,
+                             void* out, float* lse, hipStream_t stream) {
+  (void)hipGetLastError();
+  if (dtype == MC_DTYPE_BF16) {
+    const int64_t per = 256 / (Bf16::kD / 4);
+    attn_merge_kernel<Bf16><<<(unsigned)((rows + per - 1) / per), 256, 0, stream>>>(o_parts, lse_parts, kv_splits, rows, out, lse);
+  } else {
+    const int64_t per = 256 / (F32::kD / 4);
+    attn_merge_kernel<F32><<<(unsigned)((rows + per - 1) / per), 256, 0, stream>>>(o_parts, lse_parts, kv_splits, rows, out, lse);
+  }
   return hipGetLastError();
 }
 

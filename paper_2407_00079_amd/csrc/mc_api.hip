@@ -26,10 +26,10 @@ mc_status check_params(const mc_attn_params* p) {
 }
 
 // upper bound on work items: per request and KV head, ceil(C_r * G / rows) <= C_r * G / rows + 1
-size_t max_items(const mc_attn_params* p, int32_t batch, int64_t total_new_tokens) {
+size_t max_items(const mc_attn_params* p, int32_t batch, int64_t total_new_tokens, int32_t kv_splits = 1) {
   const int64_t rows = mc::attn_tile_rows(p->dtype);
   const int64_t G = p->num_q_heads / p->num_kv_heads;
-  return (size_t)(p->num_kv_heads * ((total_new_tokens * G) / rows + batch));
+  return (size_t)(p->num_kv_heads * ((total_new_tokens * G) / rows + batch)) * (size_t)kv_splits;
 }
 
 // Pinned host slots the work list is written to before its asynchronous upload.  A slot is
@@ -130,10 +130,18 @@ size_t mc_prefill_attn_workspace_bytes(const mc_attn_params* p, int32_t batch, i
   return sizeof(mc::AttnItem) * max_items(p, batch, total_new_tokens) + sizeof(mc::AttnReq) * (size_t)batch + 64;
 }
 
-mc_status mc_prefill_attn_paged(const mc_attn_params* p, const void* q, const void* k_pool, const void* v_pool,
-                                const int32_t* block_tables, int32_t max_pages_per_req,
-                                const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch, void* out,
-                                float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// kv_splits == 0: the whole-row kernel writes out / lse.  kv_splits >= 1: the split kernel writes
+// partials (out / lse unused).
+mc_status attn_enqueue(const mc_attn_params* p, const void* q, const void* k_pool, const void* v_pool,
+                       const int32_t* block_tables, int32_t max_pages_per_req, const int32_t* prefix_lens,
+                       const int32_t* new_lens, int32_t batch, void* out, float* lse, int32_t kv_splits,
+                       float* o_parts, float* lse_parts, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+  const bool split = kv_splits > 0;
   mc_status st = check_params(p);
   if (st != MC_OK) return st;
   if (batch < 0 || max_pages_per_req < 0) return MC_ERR_SHAPE;
@@ -149,14 +157,18 @@ mc_status mc_prefill_attn_paged(const mc_attn_params* p, const void* q, const vo
     total_new += new_lens[r];
   }
   if (total_new == 0) return MC_OK;
-  if (q == nullptr || k_pool == nullptr || v_pool == nullptr || block_tables == nullptr || out == nullptr)
-    return MC_ERR_NULL;
+  if (q == nullptr || k_pool == nullptr || v_pool == nullptr || block_tables == nullptr) return MC_ERR_NULL;
+  if (split ? (o_parts == nullptr || lse_parts == nullptr) : out == nullptr) return MC_ERR_NULL;
   if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out) || !aligned16(workspace) ||
-      (reinterpret_cast<uintptr_t>(block_tables) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+      !aligned16(o_parts) || (reinterpret_cast<uintptr_t>(block_tables) & 3u) ||
+      (reinterpret_cast<uintptr_t>(lse) & 3u) || (reinterpret_cast<uintptr_t>(lse_parts) & 3u))
     return MC_ERR_ALIGN;
   const int G = p->num_q_heads / p->num_kv_heads;
   if (total_new * p->num_q_heads > INT32_MAX || (int64_t)batch * max_pages_per_req > INT32_MAX) return MC_ERR_RANGE;
-  if (workspace == nullptr || workspace_bytes < mc_prefill_attn_workspace_bytes(p, batch, total_new))
+  const size_t n_max = max_items(p, batch, total_new, split ? kv_splits : 1);
+  if (n_max > (size_t)INT32_MAX) return MC_ERR_RANGE;
+  if (workspace == nullptr ||
+      workspace_bytes < sizeof(mc::AttnItem) * n_max + sizeof(mc::AttnReq) * (size_t)batch + 64)
     return MC_ERR_WORKSPACE;
 
   // ---- work list: one item per (request, KV head, tile of stacked rows), most keys first,
@@ -179,7 +191,18 @@ mc_status mc_prefill_attn_paged(const mc_attn_params* p, const void* q, const vo
     for (int32_t g = 0; g < p->num_kv_heads; ++g)
       for (int64_t row0 = 0; row0 < n_rows; row0 += rows) {
         const int64_t tok_last = std::min<int64_t>(C - 1, (row0 + rows - 1) / G);
-        lanes[(r * p->num_kv_heads + g) % kXcd].push_back({P + tok_last + 1, {r, g, (int32_t)row0, 0}});
+        const int64_t keys = P + tok_last + 1;                 // keys the tile's last row sees
+        if (!split) {
+          lanes[(r * p->num_kv_heads + g) % kXcd].push_back({keys, {r, g, (int32_t)row0, 0}});
+          continue;
+        }
+        // slices of whole 64-key tiles, ceil(tiles of the request / kv_splits) each; every slice gets
+        // an item, also one past what the tile can see (it writes zeros and -inf)
+        const int64_t per = ((((int64_t)P + C + 63) / 64) + kv_splits - 1) / kv_splits * 64;
+        for (int32_t sl = 0; sl < kv_splits; ++sl) {
+          const int64_t cost = std::max<int64_t>(0, std::min<int64_t>(keys, (sl + 1) * per) - sl * per);
+          lanes[(r * p->num_kv_heads + g + sl) % kXcd].push_back({cost, {r, g, (int32_t)row0, sl}});
+        }
       }
   }
   std::vector<mc::AttnItem> items;
@@ -234,7 +257,58 @@ mc_status mc_prefill_attn_paged(const mc_attn_params* p, const void* q, const vo
   const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale : 1.0 / std::sqrt((double)p->head_dim);
   args.scale_log2e = (float)(scale * 1.4426950408889634);
   args.n_items = (int32_t)n_items;
+  args.kv_splits = split ? kv_splits : 0;
+  args.rows_total = total_new * p->num_q_heads;
+  args.o_parts = o_parts;
+  args.lse_parts = lse_parts;
   if (mc::launch_attn(p->dtype, args, stream) != hipSuccess) return MC_ERR_HIP;
+  return MC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+mc_status mc_prefill_attn_paged(const mc_attn_params* p, const void* q, const void* k_pool, const void* v_pool,
+                                const int32_t* block_tables, int32_t max_pages_per_req,
+                                const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch, void* out,
+                                float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return attn_enqueue(p, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens, batch, out, lse,
+                      0, nullptr, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+size_t mc_prefill_attn_split_workspace_bytes(const mc_attn_params* p, int32_t batch, int64_t total_new_tokens,
+                                             int32_t kv_splits) {
+  if (check_params(p) != MC_OK || batch < 0 || total_new_tokens < 0 || kv_splits < 1 || kv_splits > MC_MAX_KV_SPLITS)
+    return 0;
+  return sizeof(mc::AttnItem) * max_items(p, batch, total_new_tokens, kv_splits) +
+         sizeof(mc::AttnReq) * (size_t)batch + 64;
+}
+
+mc_status mc_prefill_attn_paged_split(const mc_attn_params* p, const void* q, const void* k_pool,
+                                      const void* v_pool, const int32_t* block_tables, int32_t max_pages_per_req,
+                                      const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch,
+                                      int32_t kv_splits, float* o_parts, float* lse_parts, void* workspace,
+                                      size_t workspace_bytes, void* hip_stream) {
+  if (kv_splits < 1 || kv_splits > MC_MAX_KV_SPLITS) return MC_ERR_SHAPE;
+  return attn_enqueue(p, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens, batch, nullptr,
+                      nullptr, kv_splits, o_parts, lse_parts, workspace, workspace_bytes, hip_stream);
+}
+
+mc_status mc_attn_merge_lse(const float* o_parts, const float* lse_parts, int32_t kv_splits, int64_t rows,
+                            int32_t head_dim, int32_t dtype, void* out, float* lse, void* hip_stream) {
+  if (kv_splits < 1 || kv_splits > MC_MAX_KV_SPLITS || rows < 0 || head_dim <= 0) return MC_ERR_SHAPE;
+  if (!((dtype == MC_DTYPE_BF16 && head_dim == 128) || (dtype == MC_DTYPE_F32 && head_dim == 64)))
+    return MC_ERR_UNSUPPORTED;
+  if (rows == 0) return MC_OK;
+  if (o_parts == nullptr || lse_parts == nullptr || out == nullptr) return MC_ERR_NULL;
+  if (!aligned16(o_parts) || !aligned16(out) || (reinterpret_cast<uintptr_t>(lse_parts) & 3u) ||
+      (reinterpret_cast<uintptr_t>(lse) & 3u))
+    return MC_ERR_ALIGN;
+  if (rows > INT32_MAX) return MC_ERR_RANGE;
+  if (mc::launch_attn_merge(dtype, o_parts, lse_parts, kv_splits, rows, out, lse,
+                            reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return MC_ERR_HIP;
   return MC_OK;
 }
 

@@ -13,8 +13,8 @@ namespace mc {
 struct AttnItem {
   int32_t req;
   int32_t kv_head;
-  int32_t row0;  // first stacked row of the tile
-  int32_t pad;
+  int32_t row0;   // first stacked row of the tile
+  int32_t slice;  // key slice of the request this item covers (split launches only, else 0)
 };
 
 struct AttnReq {
@@ -36,6 +36,12 @@ struct AttnArgs {
   int32_t Hq, Hkv, G, max_pages;
   float scale_log2e;  // softmax scale * log2(e): scores go through exp2
   int32_t n_items;
+  // split launches (kv_splits > 0): partial results go to o_parts [kv_splits, rows_total, D] fp32 and
+  // lse_parts [kv_splits, rows_total] instead of out / lse
+  int32_t kv_splits;
+  int64_t rows_total;  // total_new_tokens * Hq
+  float* o_parts;
+  float* lse_parts;
 };
 
 // rows of stacked queries one workgroup covers, per dtype (host needs it to cut the work list)
@@ -43,6 +49,10 @@ int attn_tile_rows(int dtype);
 
 // enqueue the attention kernel over args.n_items work items
 hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream);
+
+// enqueue the merge of kv_splits partial results over `rows` rows into out (dtype) and lse (or null)
+hipError_t launch_attn_merge(int dtype, const float* o_parts, const float* lse_parts, int kv_splits, int64_t rows,
+                             void* out, float* lse, hipStream_t stream);
 
 // 16-byte vectors of a page one copy workgroup moves (host needs it for the grid-size range check)
 int kv_copy_slice_vecs();

@@ -1,0 +1,131 @@
+"""GPU parity: split attention partials and their merge against the CPU oracle (Section 5.1: attention is
+associative over slices of the keys)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_00079_amd import binding as B
+from paper_2407_00079_amd import workloads as W
+
+from gpu_util import TOL, DeviceCase, check_close, dev
+from split_util import all_rows, oracle_partials
+
+pytestmark = pytest.mark.gpu
+
+
+def run_split(case, kv_splits, scale=0.0):
+    dc = DeviceCase(case)
+    dc.params.softmax_scale = scale
+    n = case.total_new * case.num_q_heads
+    o_parts = torch.full((kv_splits, case.total_new, case.num_q_heads, case.head_dim), float("nan"),
+                         dtype=torch.float32, device="cuda:0")
+    lse_parts = torch.full((kv_splits, case.total_new, case.num_q_heads), float("nan"), dtype=torch.float32,
+                           device="cuda:0")
+    ws = torch.empty(max(B.mc_prefill_attn_split_workspace_bytes(dc.params, case.batch, case.total_new, kv_splits), 16),
+                     dtype=torch.uint8, device="cuda:0")
+    B.mc_prefill_attn_paged_split(dc.params, dc.q, dc.k_pool, dc.v_pool, dc.block_tables, case.prefix_lens.tolist(),
+                                  case.new_lens.tolist(), kv_splits, o_parts, lse_parts, ws)
+    out = torch.full_like(dc.out, float("nan"))
+    lse = torch.full_like(dc.lse, float("nan"))
+    B.mc_attn_merge_lse(o_parts, lse_parts, kv_splits, n, case.head_dim, dc.params.dtype, out, lse)
+    torch.cuda.synchronize()
+    return (o_parts.cpu().numpy().reshape(kv_splits, n, -1), lse_parts.cpu().numpy().reshape(kv_splits, n),
+            out.float().cpu().numpy().astype(np.float64).reshape(n, -1), lse.cpu().numpy().astype(np.float64).reshape(n))
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,D,prefix,new,pages,kv_splits", [
+    (W.BF16, 8, 2, 128, [700, 30], [40, 150], 128, 3),      # slices cut through prefix and chunk; ragged lengths
+    (W.BF16, 8, 1, 128, [2000], [8], 160, 7),               # small chunk against a long prefix (what splitting is for)
+    (W.BF16, 4, 4, 128, [0], [300], 32, 4),                 # no prefix: early rows see nothing of the late slices
+    (W.BF16, 8, 2, 128, [100, 5], [1, 60], 32, 16),         # more slices than tiles: trailing slices empty
+    (W.F32, 4, 1, 64, [256], [128], 64, 2),                 # the fp32 configuration
+    (W.BF16, 8, 2, 128, [130], [70], 32, 1),                # one slice = the whole row, through the partial path
+])
+def test_split_partials_and_merge_match_oracle(oracle, dtype, Hq, Hkv, D, prefix, new, pages, kv_splits):
+    print(f"split case {dtype} Hq={Hq} Hkv={Hkv} prefix={prefix} new={new} splits={kv_splits}", flush=True)
+    case = W.make_attn_case(61, dtype, Hq, Hkv, D, 16, prefix, new, pages)
+    o_parts, lse_parts, out, lse = run_split(case, kv_splits)
+    rows, ref_o, ref_l = oracle_partials(oracle, case, kv_splits)
+    # rows are (request, head, chunk row); the device order is (token, head)
+    order = np.lexsort((rows[:, 1], case.q_offsets[rows[:, 0]] + rows[:, 2]))
+    ref_o, ref_l, rows = ref_o[:, order], ref_l[:, order], rows[order]
+    tol = TOL[dtype]
+    empty = np.isneginf(ref_l)
+    # which (slice, row) pairs hold no visible key is exact; their partial is zeros and -inf
+    np.testing.assert_array_equal(np.isneginf(lse_parts), empty)
+    assert (o_parts[empty] == 0).all()
+    assert np.isfinite(o_parts).all()
+    for s in range(kv_splits):
+        keep = ~empty[s]
+        if keep.any():
+            check_close(o_parts[s][keep].astype(np.float64), ref_o[s][keep].astype(np.float64), dtype, f"slice {s}")
+            assert np.abs(lse_parts[s][keep].astype(np.float64) - ref_l[s][keep]).max() <= tol["lse_abs"]
+    # the merge kernel against the oracle's merge of the SAME (device) partials: only its own arithmetic differs
+    m_out, m_lse = oracle.attn_merge_lse(o_parts, lse_parts)
+    out_tol = 2.0 ** -8 * max(1.0, np.abs(m_out).max()) if dtype == W.BF16 else 1e-5    # one rounding to bf16
+    assert np.abs(out - m_out).max() <= out_tol
+    assert np.abs(lse - m_lse).max() <= 1e-5 * max(1.0, np.abs(m_lse).max())
+    # end to end against whole-row attention
+    whole, whole_lse, _ = oracle.case_rows(case, rows)
+    check_close(out, whole, dtype, "merged")
+    assert np.abs(lse - whole_lse).max() <= tol["lse_abs"]
+
+
+def test_split_equals_unsplit_kernel_closely(oracle):
+    # same inputs through the whole-row kernel and through 5 slices + merge: both within tolerance of the
+    # oracle, and close to each other
+    case = W.make_attn_case(62, W.BF16, 16, 2, 128, 16, [1500], [64], 128)
+    dc = DeviceCase(case)
+    dc.run()
+    out0, lse0 = dc.result()
+    _, _, out, lse = run_split(case, 5)
+    n = case.total_new * case.num_q_heads
+    assert np.abs(out - out0.reshape(n, -1)).max() <= 2e-2
+    assert np.abs(lse - lse0.reshape(n)).max() <= 2 * TOL[W.BF16]["lse_abs"]
+
+
+def test_merge_of_foreign_partials(oracle):
+    # partials that did not come from this library's kernel: -inf parts, NaN payload behind them, all-empty rows
+    rng = np.random.default_rng(8)
+    S, n, D = 6, 37, 128
+    o = rng.standard_normal((S, n, D)).astype(np.float32)
+    l = (4 * rng.standard_normal((S, n))).astype(np.float32)
+    l[2] = -np.inf
+    o[2] = np.nan
+    l[:, 5] = -np.inf
+    out = torch.full((n, D), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    lse = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda:0")
+    B.mc_attn_merge_lse(dev(o), dev(l), S, n, D, B.MC_DTYPE_BF16, out, lse)
+    torch.cuda.synchronize()
+    ref, ref_lse = oracle.attn_merge_lse(o, l)
+    got = out.float().cpu().numpy().astype(np.float64)
+    assert np.abs(got - ref).max() <= 2.0 ** -8 * max(1.0, np.abs(ref).max())
+    got_lse = lse.cpu().numpy().astype(np.float64)
+    assert np.isneginf(got_lse[5]) and (got[5] == 0).all()
+    keep = np.isfinite(ref_lse)
+    assert np.abs(got_lse[keep] - ref_lse[keep]).max() <= 1e-5 * np.abs(ref_lse[keep]).max()
+
+
+def test_split_rejections():
+    case = W.make_attn_case(63, W.BF16, 8, 1, 128, 16, [64], [16], 16)
+    dc = DeviceCase(case)
+    o_parts = torch.zeros((2, 16, 8, 128), dtype=torch.float32, device="cuda:0")
+    lse_parts = torch.zeros((2, 16, 8), dtype=torch.float32, device="cuda:0")
+    ws = torch.empty(B.mc_prefill_attn_split_workspace_bytes(dc.params, 1, 16, 2), dtype=torch.uint8, device="cuda:0")
+    for bad in (0, B.MC_MAX_KV_SPLITS + 1):
+        with pytest.raises(B.McError) as e:
+            B.mc_prefill_attn_paged_split(dc.params, dc.q, dc.k_pool, dc.v_pool, dc.block_tables, [64], [16], bad,
+                                          o_parts, lse_parts, ws)
+        assert e.value.status == B.MC_ERR_SHAPE
+    with pytest.raises(B.McError) as e:
+        B.mc_prefill_attn_paged_split(dc.params, dc.q, dc.k_pool, dc.v_pool, dc.block_tables, [64], [16], 2,
+                                      None, lse_parts, ws)
+    assert e.value.status == B.MC_ERR_NULL
+    with pytest.raises(B.McError) as e:      # workspace sized for the unsplit call
+        B.mc_prefill_attn_paged_split(dc.params, dc.q, dc.k_pool, dc.v_pool, dc.block_tables, [64], [16], 200,
+                                      o_parts, lse_parts, ws)
+    assert e.value.status == B.MC_ERR_WORKSPACE
+    with pytest.raises(B.McError) as e:
+        B.mc_attn_merge_lse(o_parts, lse_parts, 2, 128, 96, B.MC_DTYPE_BF16, dc.out, None)
+    assert e.value.status == B.MC_ERR_UNSUPPORTED
+    assert B.mc_prefill_attn_split_workspace_bytes(dc.params, 1, 16, 0) == 0
