@@ -487,20 +487,15 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
     for (int i = 0; i < kRing; ++i) ring[i] = T::load_k(kt, kb, i);
   };
 
-  // Blocks that may reach the diagonal (masked steps) are settled when their scores exist: block j
-  // arrives settled and block j+1 is settled at the end of the step.
-  //
-  // Fully visible blocks (unmasked steps) take no maxima at all.  Their probabilities are formed
+  // The pipeline only ever sees fully visible blocks, and it takes no maxima.  Probabilities are formed
   // against the reference as it stands and the block sums tell whether that was safe: a lane's sum
   // of 16 probabilities above kSumGuard (or not finite) means some score outgrew the reference by
   // more than the slack.  Only then (rare, wave-uniform) the block's scores are recomputed from
   // the tile still in LDS, the reference is raised to their true maximum and the probabilities
   // are redone; nothing has been accumulated from the discarded ones.
   constexpr float kSumGuard = 4096.0f;   // 16 probabilities of at most 2^kRescaleSlack each
-  // step(block j = (buf_cur, kb_cur); first key of block j+1; block j+2 = (buf_pre, kb_pre))
-  auto step = [&](int buf_cur, int kb_cur, int key0_nxt, int buf_pre, int kb_pre,
-                  auto masked_tag) __attribute__((always_inline)) {
-    constexpr bool kMasked = decltype(masked_tag)::value;
+  // step(block j = (buf_cur, kb_cur); block j+2 = (buf_pre, kb_pre))
+  auto step = [&](int buf_cur, int kb_cur, int buf_pre, int kb_pre) __attribute__((always_inline)) {
     const uint32_t vt = v_lane + buf_cur * kStageBytes;
     const uint32_t kt = k_lane + buf_pre * kStageBytes;
     s_cur = s_next;
@@ -524,12 +519,10 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
       __builtin_amdgcn_sched_barrier(0);
     }
     bsum = T::template round_sum<kPer>(pb, s_cur, 16 - kPer, bsum);
-    if (!kMasked) {
-      if (__builtin_amdgcn_ballot_w64(!(bsum <= kSumGuard)) != 0) {
-        qk_block(buf_cur, kb_cur, s_cur);
-        settle_reference(s_cur, 0, std::false_type{});
-        bsum = probabilities(s_cur, pb);
-      }
+    if (__builtin_amdgcn_ballot_w64(!(bsum <= kSumGuard)) != 0) {
+      qk_block(buf_cur, kb_cur, s_cur);
+      settle_reference(s_cur, 0, std::false_type{});
+      bsum = probabilities(s_cur, pb);
     }
     l_sum += bsum;
     // ---- phase B
@@ -539,7 +532,15 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
       ring[i] = T::load_k(kt, kb_pre, i);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (kMasked) settle_reference(s_next, key0_nxt, std::true_type{});
+  };
+  // One block start to finish, for the few blocks that may reach the diagonal: scores (unless the
+  // pipeline has left them in `s`), mask, true maxima and reference, probabilities, P V.
+  auto plain_block = [&](int buf, int kb, int key0, f32x16& s, bool have_scores) __attribute__((always_inline)) {
+    if (!have_scores) qk_block(buf, kb, s);
+    settle_reference(s, key0, std::true_type{});
+    typename T::pblock pb;
+    l_sum += probabilities(s, pb);
+    pv_block(buf, kb, pb);
   };
 
   load_ids(t_lo);
@@ -556,15 +557,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   // vector-memory counter only ever counts the tile copies
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
-  qk_block(0, 0, s_next);
-  settle_reference(s_next, t_lo * kTileKeys, std::true_type{});
-  load_k_ring(0, 1);
   int buf = 0;
-  // One tile = barrier, enqueue the copy of tile + 2, two steps.  After the barrier tile + 1 is
+  // One tile = barrier, enqueue the copy of tile + 2, two blocks.  After the barrier tile + 1 is
   // visible to every wave (it was enqueued a whole tile ago) and no wave reads tile - 1 any
   // more, so that buffer takes tile + 2.
-  auto tile_body = [&](int tile, bool more, auto masked_tag) __attribute__((always_inline)) {
-    const int buf_next = buf == 2 ? 0 : buf + 1;
+  auto tile_sync = [&](int tile) __attribute__((always_inline)) {
     const bool ahead = tile + 2 < n_tiles;
     if (ahead) load_ids(tile + 3);
     copies_landed();
@@ -573,26 +570,33 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
       fetch(tile + 2, buf == 0 ? 2 : buf - 1);   // (tile + 2) % 3, ids loaded one tile ago
       take_ids();
     }
-    // block 0: scores of block 1 (same tile), then the K fragments of the next tile's block 0
-    // (on the last tile that buffer holds stale but in-bounds data nobody uses)
-    step(buf, 0, tile * kTileKeys + 32, buf_next, 0, masked_tag);
-    if (more) {
-      // block 1: scores of the next tile's block 0, then the K fragments of its block 1
-      step(buf, 1, (tile + 1) * kTileKeys, buf_next, 1, masked_tag);
-    } else {
-      typename T::pblock pb;
-      l_sum += probabilities(s_next, pb);
-      pv_block(buf, 1, pb);
-    }
-    buf = buf_next;
   };
   int tile = t_lo;
-  // tiles every key of which is visible to every row (never the last tile: it ends the pipeline)
+  // tiles every key of which is visible to every row go through the pipeline (never the last
+  // tile: the pipeline always computes the scores of one block ahead)
   const int n_plain = n_free < n_tiles - 1 ? n_free : n_tiles - 1;
-  for (; tile < n_plain; ++tile) tile_body(tile, true, std::false_type{});
-  // the rest reach the diagonal; their first block has not been settled by an unmasked step
-  if (tile > t_lo) settle_reference(s_next, tile * kTileKeys, std::true_type{});
-  for (; tile < n_tiles; ++tile) tile_body(tile, tile + 1 < n_tiles, std::true_type{});
+  qk_block(0, 0, s_next);
+  if (tile < n_plain) {
+    settle_reference(s_next, 0, std::false_type{});
+    load_k_ring(0, 1);
+    for (; tile < n_plain; ++tile) {
+      const int buf_next = buf == 2 ? 0 : buf + 1;
+      tile_sync(tile);
+      step(buf, 0, buf_next, 0);   // block 0: scores of block 1, then the K fragments of the next tile's block 0
+      step(buf, 1, buf_next, 1);   // block 1: scores of the next tile's block 0, then the K fragments of its block 1
+      buf = buf_next;
+    }
+  }
+  // the rest may reach the diagonal: block at a time; the scores of the first such block are in s_next
+  bool have_scores = true;
+  for (; tile < n_tiles; ++tile) {
+    const int buf_next = buf == 2 ? 0 : buf + 1;
+    tile_sync(tile);
+    plain_block(buf, 0, tile * kTileKeys, s_next, have_scores);
+    have_scores = false;
+    plain_block(buf, 1, tile * kTileKeys + 32, s_next, false);
+    buf = buf_next;
+  }
   const float l_run = sum_with_other_half(l_sum);
 
   // ---- epilogue: normalise, round, store; lane holds 4 consecutive columns per (db, r/4)
