@@ -262,6 +262,65 @@ def main():
                                      "frac": round(ab / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "us_per_launch": round(us, 2),
                                      "bytes_per_launch": ab, "traffic": None,
                                      "note": "same buffers every launch: the working set fits the 256 MiB last-level cache"}
+        # the same layer-wise step against the HOST pool: a layer's pages come from pinned host memory before its
+        # attention and go back after it (load on one side stream, store on another, attention on the compute stream)
+        HL = min(4, LAY)
+        kh_in = [torch.empty((n, pb), dtype=torch.uint8, pin_memory=True) for _ in range(HL)]
+        vh_in = [torch.empty((n, pb), dtype=torch.uint8, pin_memory=True) for _ in range(HL)]
+        kh_out = [torch.empty((n, pb), dtype=torch.uint8, pin_memory=True) for _ in range(HL)]
+        vh_out = [torch.empty((n, pb), dtype=torch.uint8, pin_memory=True) for _ in range(HL)]
+        for t in kh_in + vh_in:
+            t.random_(0, 256)
+        st_load, st_store = torch.cuda.Stream(), torch.cuda.Stream()
+
+        def host_steps(count):
+            loaded = [torch.cuda.Event() for _ in range(count + 1)]
+            attended = [torch.cuda.Event() for _ in range(count)]
+            B.mc_kv_load_layer(kh_in[0], vh_in[0], k_remote[0], v_remote[0], N2, pb, dst_ids, n, k_pool[0], v_pool[0],
+                               st_load)
+            loaded[0].record(st_load)
+            for i in range(count):
+                l, ln = i % HL, (i + 1) % HL
+                if i + 1 < count:
+                    B.mc_kv_load_layer(kh_in[ln], vh_in[ln], k_remote[ln], v_remote[ln], N2, pb, dst_ids, n, k_pool[ln],
+                                       v_pool[ln], st_load)
+                    loaded[i + 1].record(st_load)
+                compute.wait_event(loaded[i])
+                attn.append(compute)
+                attn.launch(compute)
+                attended[i].record(compute)
+                st_store.wait_event(attended[i])
+                B.mc_kv_store_layer(k_pool[l], v_pool[l], N2, pb, dst_ids, n, k_store[l], v_store[l], kh_out[l],
+                                    vh_out[l], st_store)
+
+        host_steps(4)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        host_steps(12)
+        torch.cuda.synchronize()
+        ms_host = (time.perf_counter() - t0) * 1e3 / 12
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        ev[0].record(st_load)
+        for l in range(HL):
+            B.mc_kv_load_layer(kh_in[l], vh_in[l], k_remote[l], v_remote[l], N2, pb, dst_ids, n, k_pool[l], v_pool[l], st_load)
+        ev[1].record(st_load)
+        torch.cuda.synchronize()
+        ev[2].record(st_store)
+        for l in range(HL):
+            B.mc_kv_store_layer(k_pool[l], v_pool[l], N2, pb, dst_ids, n, k_store[l], v_store[l], kh_out[l], vh_out[l], st_store)
+        ev[3].record(st_store)
+        torch.cuda.synchronize()
+        layer_bytes = 2 * n * pb
+        result["host_streaming"] = {
+            "what": "the step with each layer's 2048 pages (K and V, 32 KiB each) loaded from and stored to pinned host "
+                    "memory: load and store on two side streams, append + attention on the compute stream",
+            "ms_per_step": round(ms_host, 4), "attn_tflops": round(attn.flops / (ms_host * 1e-3) / 1e12, 1),
+            "load_layer_ms_alone": round(ev[0].elapsed_time(ev[1]) / HL, 3),
+            "load_GBs_alone": round(layer_bytes / (ev[0].elapsed_time(ev[1]) / HL * 1e-3) / 1e9, 1),
+            "store_layer_ms_alone": round(ev[2].elapsed_time(ev[3]) / HL, 3),
+            "store_GBs_alone": round(layer_bytes / (ev[2].elapsed_time(ev[3]) / HL * 1e-3) / 1e9, 1),
+            "bytes_per_layer_per_direction": layer_bytes}
+        del kh_in, vh_in, kh_out, vh_out
         labels = {3: "config 3: 8/1 heads, P=122880, C=8192 (128k context)",
                   4: "config 4: 16 requests, 64/8 heads, prefixes U[0,32768] (page multiples), chunks lognormal(median 2048)"}
         del attn.q, attn.k, attn.v, attn.out, attn.k_new, attn.v_new

@@ -207,6 +207,30 @@ mc_status mc_kv_unpack_layer(const void* k_in, const void* v_in, int64_t num_pag
                              int64_t page_bytes, const int32_t* page_ids, int64_t n,
                              void* k_pool_layer, void* v_pool_layer, void* hip_stream);
 
+/*
+ * Layer-wise prefill against the CPU-DRAM KVCache pool (Section 5.2: a layer's KVCache is loaded
+ * before its attention and stored after it, asynchronously; Section 3 steps 1 and 3: the prefix
+ * comes from, and the new KVCache goes back to, host memory).  One layer, one direction, all on
+ * `hip_stream`:
+ *
+ *   load:  k_host/v_host (n packed pages each) -> k_stage/v_stage -> pages page_ids[i] of the pools
+ *          = two host-to-device copies, then mc_kv_unpack_layer
+ *   store: pages page_ids[i] of the pools -> k_stage/v_stage -> k_host/v_host
+ *          = mc_kv_pack_layer, then two device-to-host copies
+ *
+ *   k_host, v_host    host  n * page_bytes each.  For the copies to be asynchronous the memory
+ *                           must be pinned (hipHostMalloc); pageable memory works but blocks.
+ *                           The caller keeps it valid until the stream has passed the call.
+ *   k_stage, v_stage  dev   n * page_bytes each, the packed form in HBM
+ *   the rest as in mc_kv_unpack_layer / mc_kv_pack_layer, same status codes.
+ */
+mc_status mc_kv_load_layer(const void* k_host, const void* v_host, void* k_stage, void* v_stage,
+                           int64_t num_pages, int64_t page_bytes, const int32_t* page_ids, int64_t n,
+                           void* k_pool_layer, void* v_pool_layer, void* hip_stream);
+mc_status mc_kv_store_layer(const void* k_pool_layer, const void* v_pool_layer, int64_t num_pages,
+                            int64_t page_bytes, const int32_t* page_ids, int64_t n, void* k_stage,
+                            void* v_stage, void* k_host, void* v_host, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

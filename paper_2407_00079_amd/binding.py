@@ -20,7 +20,8 @@ MC_DTYPE_BF16, MC_DTYPE_F32 = 0, 1
 
 EXPORTS = ("mc_status_string", "mc_prefill_attn_workspace_bytes", "mc_prefill_attn_paged",
            "mc_kv_pack_layer", "mc_kv_unpack_layer", "mc_kv_append_workspace_bytes", "mc_kv_append_paged",
-           "mc_prefill_attn_split_workspace_bytes", "mc_prefill_attn_paged_split", "mc_attn_merge_lse")
+           "mc_prefill_attn_split_workspace_bytes", "mc_prefill_attn_paged_split", "mc_attn_merge_lse",
+           "mc_kv_load_layer", "mc_kv_store_layer")
 MC_MAX_KV_SPLITS = 256
 
 
@@ -72,6 +73,10 @@ def lib():
         l.mc_prefill_attn_paged_split.restype = ctypes.c_int
         l.mc_prefill_attn_paged_split.argtypes = [ctypes.POINTER(McAttnParams), vp, vp, vp, vp, i32, vp, vp, i32, i32,
                                                   vp, vp, vp, ctypes.c_size_t, vp]
+        l.mc_kv_load_layer.restype = ctypes.c_int
+        l.mc_kv_load_layer.argtypes = [vp, vp, vp, vp, i64, i64, vp, i64, vp, vp, vp]
+        l.mc_kv_store_layer.restype = ctypes.c_int
+        l.mc_kv_store_layer.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, vp, vp, vp]
         l.mc_attn_merge_lse.restype = ctypes.c_int
         l.mc_attn_merge_lse.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp]
         _lib = l
@@ -190,6 +195,38 @@ def mc_kv_unpack_layer(k_in, v_in, num_pages: int, page_bytes: int, page_ids, n:
                                 _dev_ptr(k_pool_layer), _dev_ptr(v_pool_layer), _stream_handle(stream))
     if st != MC_OK:
         raise McError(st, "mc_kv_unpack_layer")
+
+
+def mc_kv_load_layer_raw(k_host, v_host, k_stage, v_stage, num_pages, page_bytes, page_ids, n, k_pool, v_pool,
+                         hip_stream) -> int:
+    return int(lib().mc_kv_load_layer(k_host, v_host, k_stage, v_stage, num_pages, page_bytes, page_ids, n, k_pool,
+                                      v_pool, hip_stream))
+
+
+def mc_kv_store_layer_raw(k_pool, v_pool, num_pages, page_bytes, page_ids, n, k_stage, v_stage, k_host, v_host,
+                          hip_stream) -> int:
+    return int(lib().mc_kv_store_layer(k_pool, v_pool, num_pages, page_bytes, page_ids, n, k_stage, v_stage, k_host,
+                                       v_host, hip_stream))
+
+
+def mc_kv_load_layer(k_host, v_host, k_stage, v_stage, num_pages: int, page_bytes: int, page_ids, n: int,
+                     k_pool_layer, v_pool_layer, stream=None) -> None:
+    """Host (pinned torch tensors) -> staging -> the listed pool pages, enqueued on ``stream``."""
+    st = mc_kv_load_layer_raw(_dev_ptr(k_host), _dev_ptr(v_host), _dev_ptr(k_stage), _dev_ptr(v_stage), num_pages,
+                              page_bytes, _dev_ptr(page_ids), n, _dev_ptr(k_pool_layer), _dev_ptr(v_pool_layer),
+                              _stream_handle(stream))
+    if st != MC_OK:
+        raise McError(st, "mc_kv_load_layer")
+
+
+def mc_kv_store_layer(k_pool_layer, v_pool_layer, num_pages: int, page_bytes: int, page_ids, n: int, k_stage,
+                      v_stage, k_host, v_host, stream=None) -> None:
+    """The listed pool pages -> staging -> host (pinned torch tensors), enqueued on ``stream``."""
+    st = mc_kv_store_layer_raw(_dev_ptr(k_pool_layer), _dev_ptr(v_pool_layer), num_pages, page_bytes,
+                               _dev_ptr(page_ids), n, _dev_ptr(k_stage), _dev_ptr(v_stage), _dev_ptr(k_host),
+                               _dev_ptr(v_host), _stream_handle(stream))
+    if st != MC_OK:
+        raise McError(st, "mc_kv_store_layer")
 
 
 def mc_kv_append_workspace_bytes(batch: int) -> int:

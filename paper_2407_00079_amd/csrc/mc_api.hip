@@ -399,4 +399,39 @@ mc_status mc_kv_unpack_layer(const void* k_in, const void* v_in, int64_t num_pag
   return MC_OK;
 }
 
+
+mc_status mc_kv_load_layer(const void* k_host, const void* v_host, void* k_stage, void* v_stage, int64_t num_pages,
+                           int64_t page_bytes, const int32_t* page_ids, int64_t n, void* k_pool_layer,
+                           void* v_pool_layer, void* hip_stream) {
+  mc_status st = check_copy(k_stage, v_stage, num_pages, page_bytes, page_ids, n, k_pool_layer, v_pool_layer);
+  if (st != MC_OK || n == 0 || page_bytes == 0) return st;
+  if (k_host == nullptr || v_host == nullptr) return MC_ERR_NULL;
+  if (!aligned16(k_host) || !aligned16(v_host)) return MC_ERR_ALIGN;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  const size_t bytes = (size_t)n * (size_t)page_bytes;
+  if (hipMemcpyAsync(k_stage, k_host, bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
+  if (hipMemcpyAsync(v_stage, v_host, bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
+  if (mc::launch_kv_copy(false, k_stage, v_stage, k_pool_layer, v_pool_layer, page_ids, n, page_bytes, stream) !=
+      hipSuccess)
+    return MC_ERR_HIP;
+  return MC_OK;
+}
+
+mc_status mc_kv_store_layer(const void* k_pool_layer, const void* v_pool_layer, int64_t num_pages,
+                            int64_t page_bytes, const int32_t* page_ids, int64_t n, void* k_stage, void* v_stage,
+                            void* k_host, void* v_host, void* hip_stream) {
+  mc_status st = check_copy(k_pool_layer, v_pool_layer, num_pages, page_bytes, page_ids, n, k_stage, v_stage);
+  if (st != MC_OK || n == 0 || page_bytes == 0) return st;
+  if (k_host == nullptr || v_host == nullptr) return MC_ERR_NULL;
+  if (!aligned16(k_host) || !aligned16(v_host)) return MC_ERR_ALIGN;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  const size_t bytes = (size_t)n * (size_t)page_bytes;
+  if (mc::launch_kv_copy(true, k_pool_layer, v_pool_layer, k_stage, v_stage, page_ids, n, page_bytes, stream) !=
+      hipSuccess)
+    return MC_ERR_HIP;
+  if (hipMemcpyAsync(k_host, k_stage, bytes, hipMemcpyDeviceToHost, stream) != hipSuccess) return MC_ERR_HIP;
+  if (hipMemcpyAsync(v_host, v_stage, bytes, hipMemcpyDeviceToHost, stream) != hipSuccess) return MC_ERR_HIP;
+  return MC_OK;
+}
+
 }  // extern "C"
