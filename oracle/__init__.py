@@ -52,6 +52,12 @@ def _load():
             f.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, i32]
         lib.mco_kv_append_paged.restype = ctypes.c_int
         lib.mco_kv_append_paged.argtypes = [vp, vp, vp, vp, i64, vp, i32, vp, vp, i32, i32, i32, i64]
+        lib.mco_mix64.restype = ctypes.c_uint64
+        lib.mco_mix64.argtypes = [ctypes.c_uint64]
+        lib.mco_prefix_hash.restype = ctypes.c_int64
+        lib.mco_prefix_hash.argtypes = [vp, vp, i32, i32, vp]
+        lib.mco_prefix_match.restype = ctypes.c_int
+        lib.mco_prefix_match.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp]
         lib.mco_attn_merge_lse.restype = ctypes.c_int
         lib.mco_attn_merge_lse.argtypes = [vp, vp, i32, i64, i32, vp, vp]
         _lib = lib
@@ -212,3 +218,42 @@ def attn_merge_lse(o_parts: np.ndarray, lse_parts: np.ndarray):
     if rc != 0:
         raise ValueError("oracle rejected its arguments")
     return out, lse
+
+
+def mix64(x: int) -> int:
+    """The 64-bit mixing function the prefix keys are built from (the splitmix64 output function)."""
+    return int(_load().mco_mix64(ctypes.c_uint64(x & 0xFFFFFFFFFFFFFFFF)))
+
+
+def prefix_hash(tokens, tok_offsets, block_tokens: int = 512):
+    """Chained block keys of every request: (keys uint64 [total_blocks], key_offsets int64 [batch + 1])."""
+    lib = _load()
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    off = np.ascontiguousarray(tok_offsets, dtype=np.int64)
+    batch = off.shape[0] - 1
+    blocks = (-(-np.diff(off) // block_tokens)) if batch > 0 else np.zeros(0, dtype=np.int64)
+    key_off = np.zeros(batch + 1, dtype=np.int64)
+    np.cumsum(blocks, out=key_off[1:])
+    keys = np.zeros(int(key_off[-1]), dtype=np.uint64)
+    n = lib.mco_prefix_hash(_ptr(tokens), _ptr(off), batch, block_tokens, _ptr(keys))
+    if n != keys.shape[0]:
+        raise ValueError("oracle rejected its arguments")
+    return keys, key_off
+
+
+def prefix_match(keys, key_offsets, cache_keys, cache_offsets):
+    """(prefix_len int32 [batch, n_inst], best_len int32 [batch], best_inst int32 [batch])."""
+    lib = _load()
+    keys = np.ascontiguousarray(keys, dtype=np.uint64)
+    koff = np.ascontiguousarray(key_offsets, dtype=np.int64)
+    ck = np.ascontiguousarray(cache_keys, dtype=np.uint64)
+    coff = np.ascontiguousarray(cache_offsets, dtype=np.int64)
+    batch, n_inst = koff.shape[0] - 1, coff.shape[0] - 1
+    plen = np.zeros((batch, n_inst), dtype=np.int32)
+    best_len = np.zeros(batch, dtype=np.int32)
+    best_inst = np.zeros(batch, dtype=np.int32)
+    rc = lib.mco_prefix_match(_ptr(keys), _ptr(koff), batch, _ptr(ck), _ptr(coff), n_inst, _ptr(plen), _ptr(best_len),
+                              _ptr(best_inst))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return plen, best_len, best_inst

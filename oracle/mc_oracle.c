@@ -304,3 +304,90 @@ int mco_attn_merge_lse(const float* o_parts, const float* lse_parts, int n_parts
   }
   return 0;
 }
+
+/*
+ * Prefix block keys (Section 6.1 / Algorithm 1, PrefixHash; Figure "KVCache pool": a block's
+ * hash value is determined by its own hash and by its prefix).  The paper fixes the block size
+ * (512 tokens) but not the hash; the reading taken here, in 64-bit wrap-around arithmetic:
+ *
+ *   mix(x)      = the splitmix64 output function: x += 0x9E3779B97F4A7C15;
+ *                 x = (x ^ x >> 30) * 0xBF58476D1CE4E5B9; x = (x ^ x >> 27) * 0x94D049BB133111EB;
+ *                 x ^ x >> 31
+ *   digest(b)   = mix( n_b + sum_j mix( (uint64) token_j  +  (j << 32) ) ),  j = 0 .. n_b - 1 inside
+ *                 block b, n_b = its token count (a block's OWN hash: position-salted, hence
+ *                 order-sensitive; a plain sum, so it can be formed in any order)
+ *   key(0)      = mix( digest(0) ^ 0x243F6A8885A308D3 )
+ *   key(b)      = mix( digest(b) ^ rotl(key(b-1), 23) * 0x9E3779B97F4A7C15 )     (the prefix enters)
+ *
+ * Every block gets a key, the last one of a request may be partial (the two request samples
+ * the paper prints in Section 4 carry ceil(input_length / 512) ids): request r has
+ * ceil(len_r / B) keys, written back to back.  tok_offsets has batch + 1 entries.  Returns the
+ * number of keys, or -1 on a bad argument.
+ */
+static uint64_t mix64(uint64_t x) {
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+
+uint64_t mco_mix64(uint64_t x) { return mix64(x); }
+
+int64_t mco_prefix_hash(const int32_t* tokens, const int64_t* tok_offsets, int batch, int block_tokens,
+                        uint64_t* keys) {
+  if (batch < 0 || block_tokens <= 0) return -1;
+  for (int r = 0; r < batch; ++r)
+    if (tok_offsets[r + 1] < tok_offsets[r]) return -1;
+  int64_t n = 0;
+  for (int r = 0; r < batch; ++r) {
+    const int32_t* t = tokens + tok_offsets[r];
+    const int64_t len = tok_offsets[r + 1] - tok_offsets[r];
+    const int64_t blocks = (len + block_tokens - 1) / block_tokens;
+    uint64_t prev = 0;
+    for (int64_t b = 0; b < blocks; ++b) {
+      const int64_t nb = len - b * block_tokens < block_tokens ? len - b * block_tokens : block_tokens;
+      uint64_t sum = (uint64_t)nb;
+      for (int64_t j = 0; j < nb; ++j)
+        sum += mix64((uint64_t)(uint32_t)t[b * block_tokens + j] + ((uint64_t)j << 32));
+      const uint64_t digest = mix64(sum);
+      const uint64_t key = b == 0 ? mix64(digest ^ 0x243F6A8885A308D3ull)
+                                  : mix64(digest ^ (((prev << 23) | (prev >> 41)) * 0x9E3779B97F4A7C15ull));
+      keys[n++] = key;
+      prev = key;
+    }
+  }
+  return n;
+}
+
+/*
+ * Longest prefix match of every request against every prefill instance's cache keys
+ * (Algorithm 1, FindBestPrefixMatch: the request's block keys are compared one by one against
+ * the instance's cache keys).  prefix_len[r][i] = number of LEADING keys of request r that
+ * instance i holds (the first key it does not hold ends the match); best_len[r] = the largest of
+ * them, best_inst[r] = the lowest instance index that attains it (-1 if n_inst == 0).
+ * Plain scans: every request key against every cache key of the instance, in order.
+ */
+int mco_prefix_match(const uint64_t* keys, const int64_t* key_offsets, int batch, const uint64_t* cache_keys,
+                     const int64_t* cache_offsets, int n_inst, int32_t* prefix_len, int32_t* best_len,
+                     int32_t* best_inst) {
+  if (batch < 0 || n_inst < 0) return -1;
+  for (int r = 0; r < batch; ++r) {
+    best_len[r] = 0;
+    best_inst[r] = n_inst > 0 ? 0 : -1;
+    for (int i = 0; i < n_inst; ++i) {
+      int32_t len = 0;
+      for (int64_t b = key_offsets[r]; b < key_offsets[r + 1]; ++b) {
+        int found = 0;
+        for (int64_t c = cache_offsets[i]; c < cache_offsets[i + 1] && !found; ++c) found = cache_keys[c] == keys[b];
+        if (!found) break;
+        ++len;
+      }
+      prefix_len[(int64_t)r * n_inst + i] = len;
+      if (len > best_len[r]) {
+        best_len[r] = len;
+        best_inst[r] = i;
+      }
+    }
+  }
+  return 0;
+}
