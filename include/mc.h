@@ -231,6 +231,48 @@ mc_status mc_kv_store_layer(const void* k_pool_layer, const void* v_pool_layer, 
                             int64_t page_bytes, const int32_t* page_ids, int64_t n, void* k_stage,
                             void* v_stage, void* k_host, void* v_host, void* hip_stream);
 
+/*
+ * Prefix block keys (Algorithm 1, PrefixHash; Figure "KVCache pool": a block's hash value is
+ * determined by its own hash and by its prefix; Section 4: blocks of 512 tokens, one id per
+ * block, the last block of a prompt may be partial).  The paper does not fix the hash; this one,
+ * in 64-bit wrap-around arithmetic:
+ *
+ *   mix(x)    = x += 0x9E3779B97F4A7C15; x = (x ^ x >> 30) * 0xBF58476D1CE4E5B9;
+ *               x = (x ^ x >> 27) * 0x94D049BB133111EB; return x ^ x >> 31      (splitmix64 output)
+ *   digest(b) = mix( n_b + sum_{j < n_b} mix( (uint64)(uint32) token_j + (j << 32) ) ),  n_b tokens in block b
+ *   key(0)    = mix( digest(0) ^ 0x243F6A8885A308D3 )
+ *   key(b)    = mix( digest(b) ^ rotl64(key(b-1), 23) * 0x9E3779B97F4A7C15 )
+ *
+ *   tokens       dev   int32, requests back to back
+ *   tok_offsets  host  [batch + 1], request r = tokens[tok_offsets[r] .. tok_offsets[r+1])
+ *   keys         dev   uint64, request r's ceil(len_r / block_tokens) keys back to back in request order
+ *   workspace    dev   >= mc_prefix_hash_workspace_bytes(batch), 16-byte aligned
+ */
+size_t mc_prefix_hash_workspace_bytes(int32_t batch);
+mc_status mc_prefix_hash(const int32_t* tokens, const int64_t* tok_offsets, int32_t batch, int32_t block_tokens,
+                         uint64_t* keys, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Longest prefix match (Algorithm 1, FindBestPrefixMatch: a request's block keys are compared
+ * one by one against each prefill instance's cache keys).
+ *
+ *   keys          dev   uint64, request r = keys[key_offsets[r] .. key_offsets[r+1])
+ *   key_offsets   host  [batch + 1]
+ *   cache_keys    dev   uint64, instance i = cache_keys[cache_offsets[i] .. cache_offsets[i+1]),
+ *                       ASCENDING within an instance (not checked: undefined result otherwise)
+ *   cache_offsets host  [n_inst + 1]
+ *   prefix_len    dev   int32 [batch, n_inst]: number of LEADING keys of request r that instance
+ *                       i holds (the first key it lacks ends the match)
+ *   best_len      dev   int32 [batch]: the largest of them (0 if n_inst == 0)
+ *   best_inst     dev   int32 [batch]: the lowest instance index attaining it (-1 if n_inst == 0)
+ *   workspace     dev   >= mc_prefix_match_workspace_bytes(batch, n_inst), 16-byte aligned
+ */
+size_t mc_prefix_match_workspace_bytes(int32_t batch, int32_t n_inst);
+mc_status mc_prefix_match(const uint64_t* keys, const int64_t* key_offsets, int32_t batch,
+                          const uint64_t* cache_keys, const int64_t* cache_offsets, int32_t n_inst,
+                          int32_t* prefix_len, int32_t* best_len, int32_t* best_inst, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

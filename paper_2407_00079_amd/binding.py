@@ -21,7 +21,8 @@ MC_DTYPE_BF16, MC_DTYPE_F32 = 0, 1
 EXPORTS = ("mc_status_string", "mc_prefill_attn_workspace_bytes", "mc_prefill_attn_paged",
            "mc_kv_pack_layer", "mc_kv_unpack_layer", "mc_kv_append_workspace_bytes", "mc_kv_append_paged",
            "mc_prefill_attn_split_workspace_bytes", "mc_prefill_attn_paged_split", "mc_attn_merge_lse",
-           "mc_kv_load_layer", "mc_kv_store_layer")
+           "mc_kv_load_layer", "mc_kv_store_layer", "mc_prefix_hash_workspace_bytes", "mc_prefix_hash",
+           "mc_prefix_match_workspace_bytes", "mc_prefix_match")
 MC_MAX_KV_SPLITS = 256
 
 
@@ -77,6 +78,14 @@ def lib():
         l.mc_kv_load_layer.argtypes = [vp, vp, vp, vp, i64, i64, vp, i64, vp, vp, vp]
         l.mc_kv_store_layer.restype = ctypes.c_int
         l.mc_kv_store_layer.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, vp, vp, vp]
+        l.mc_prefix_hash_workspace_bytes.restype = ctypes.c_size_t
+        l.mc_prefix_hash_workspace_bytes.argtypes = [i32]
+        l.mc_prefix_hash.restype = ctypes.c_int
+        l.mc_prefix_hash.argtypes = [vp, vp, i32, i32, vp, vp, ctypes.c_size_t, vp]
+        l.mc_prefix_match_workspace_bytes.restype = ctypes.c_size_t
+        l.mc_prefix_match_workspace_bytes.argtypes = [i32, i32]
+        l.mc_prefix_match.restype = ctypes.c_int
+        l.mc_prefix_match.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         l.mc_attn_merge_lse.restype = ctypes.c_int
         l.mc_attn_merge_lse.argtypes = [vp, vp, i32, i64, i32, i32, vp, vp, vp]
         _lib = l
@@ -227,6 +236,54 @@ def mc_kv_store_layer(k_pool_layer, v_pool_layer, num_pages: int, page_bytes: in
                                _dev_ptr(v_host), _stream_handle(stream))
     if st != MC_OK:
         raise McError(st, "mc_kv_store_layer")
+
+
+def mc_prefix_hash_workspace_bytes(batch: int) -> int:
+    return int(lib().mc_prefix_hash_workspace_bytes(batch))
+
+
+def mc_prefix_match_workspace_bytes(batch: int, n_inst: int) -> int:
+    return int(lib().mc_prefix_match_workspace_bytes(batch, n_inst))
+
+
+def _i64_array(values):
+    arr = (ctypes.c_int64 * max(len(values), 1))(*[int(x) for x in values])
+    return arr, ctypes.cast(arr, ctypes.c_void_p)
+
+
+def mc_prefix_hash_raw(tokens, tok_offsets, batch, block_tokens, keys, workspace, workspace_bytes, hip_stream) -> int:
+    return int(lib().mc_prefix_hash(tokens, tok_offsets, batch, block_tokens, keys, workspace, workspace_bytes,
+                                    hip_stream))
+
+
+def mc_prefix_hash(tokens, tok_offsets, block_tokens: int, keys, workspace, stream=None) -> None:
+    """Enqueue the block keys of every request: ``tokens`` int32 device tensor, ``tok_offsets`` host sequence of
+    batch + 1 ints, ``keys`` int64 device tensor (the uint64 bit patterns) with one entry per block."""
+    keep, off = _i64_array(tok_offsets)
+    ws_bytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    st = mc_prefix_hash_raw(_dev_ptr(tokens), off, len(tok_offsets) - 1, block_tokens, _dev_ptr(keys),
+                            _dev_ptr(workspace), ws_bytes, _stream_handle(stream))
+    if st != MC_OK:
+        raise McError(st, "mc_prefix_hash")
+
+
+def mc_prefix_match_raw(keys, key_offsets, batch, cache_keys, cache_offsets, n_inst, prefix_len, best_len, best_inst,
+                        workspace, workspace_bytes, hip_stream) -> int:
+    return int(lib().mc_prefix_match(keys, key_offsets, batch, cache_keys, cache_offsets, n_inst, prefix_len, best_len,
+                                     best_inst, workspace, workspace_bytes, hip_stream))
+
+
+def mc_prefix_match(keys, key_offsets, cache_keys, cache_offsets, prefix_len, best_len, best_inst, workspace,
+                    stream=None) -> None:
+    """Enqueue the longest-prefix match of every request against every instance (device tensors; offsets on the host)."""
+    keep_k, koff = _i64_array(key_offsets)
+    keep_c, coff = _i64_array(cache_offsets)
+    ws_bytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    st = mc_prefix_match_raw(_dev_ptr(keys), koff, len(key_offsets) - 1, _dev_ptr(cache_keys), coff,
+                             len(cache_offsets) - 1, _dev_ptr(prefix_len), _dev_ptr(best_len), _dev_ptr(best_inst),
+                             _dev_ptr(workspace), ws_bytes, _stream_handle(stream))
+    if st != MC_OK:
+        raise McError(st, "mc_prefix_match")
 
 
 def mc_kv_append_workspace_bytes(batch: int) -> int:

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libmooncake_hip.so")
 PROBE = os.path.join(PKG, "mfma_ceiling")          # stand-alone measurement aid used by bench.py
-SOURCES = ["mc_api.hip", "attn_prefill.hip", "kv_copy.hip"]
+SOURCES = ["mc_api.hip", "attn_prefill.hip", "kv_copy.hip", "prefix_hash.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off on purpose (device code only)

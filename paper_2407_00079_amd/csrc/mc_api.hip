@@ -434,4 +434,90 @@ mc_status mc_kv_store_layer(const void* k_pool_layer, const void* v_pool_layer, 
   return MC_OK;
 }
 
+
+size_t mc_prefix_hash_workspace_bytes(int32_t batch) {
+  return batch < 0 ? 0 : 2 * sizeof(int64_t) * ((size_t)batch + 1) + 64;
+}
+
+mc_status mc_prefix_hash(const int32_t* tokens, const int64_t* tok_offsets, int32_t batch, int32_t block_tokens,
+                         uint64_t* keys, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (batch < 0 || block_tokens <= 0) return MC_ERR_SHAPE;
+  if (batch == 0) return MC_OK;
+  if (tok_offsets == nullptr) return MC_ERR_NULL;
+  std::vector<int64_t> tab(2 * ((size_t)batch + 1));
+  int64_t* key_off = tab.data() + batch + 1;
+  key_off[0] = 0;
+  for (int32_t r = 0; r < batch; ++r) {
+    const int64_t len = tok_offsets[r + 1] - tok_offsets[r];
+    if (len < 0 || tok_offsets[r] < 0) return MC_ERR_SHAPE;
+    key_off[r + 1] = key_off[r] + (len + block_tokens - 1) / block_tokens;
+  }
+  const int64_t total_blocks = key_off[batch];
+  if (total_blocks == 0) return MC_OK;
+  if (tokens == nullptr || keys == nullptr) return MC_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(tokens) & 3u) || (reinterpret_cast<uintptr_t>(keys) & 7u) ||
+      (reinterpret_cast<uintptr_t>(workspace) & 15u))
+    return MC_ERR_ALIGN;
+  if (total_blocks > (int64_t)INT32_MAX * 4 - 8) return MC_ERR_RANGE;
+  if (workspace == nullptr || workspace_bytes < mc_prefix_hash_workspace_bytes(batch)) return MC_ERR_WORKSPACE;
+  std::memcpy(tab.data(), tok_offsets, sizeof(int64_t) * ((size_t)batch + 1));
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  const size_t up = sizeof(int64_t) * tab.size();
+  int slot = -1;
+  void* host = g_staging.acquire(up, &slot);
+  if (host == nullptr) return MC_ERR_HIP;
+  std::memcpy(host, tab.data(), up);
+  if (hipMemcpyAsync(workspace, host, up, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
+  if (!g_staging.release_after(slot, stream)) return MC_ERR_HIP;
+  const int64_t* dev_tab = reinterpret_cast<const int64_t*>(workspace);
+  if (mc::launch_prefix_hash(tokens, dev_tab, dev_tab + batch + 1, batch, block_tokens, total_blocks, keys, stream) !=
+      hipSuccess)
+    return MC_ERR_HIP;
+  return MC_OK;
+}
+
+size_t mc_prefix_match_workspace_bytes(int32_t batch, int32_t n_inst) {
+  return (batch < 0 || n_inst < 0) ? 0 : sizeof(int64_t) * ((size_t)batch + 1 + (size_t)n_inst + 1) + 64;
+}
+
+mc_status mc_prefix_match(const uint64_t* keys, const int64_t* key_offsets, int32_t batch, const uint64_t* cache_keys,
+                          const int64_t* cache_offsets, int32_t n_inst, int32_t* prefix_len, int32_t* best_len,
+                          int32_t* best_inst, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (batch < 0 || n_inst < 0) return MC_ERR_SHAPE;
+  if (batch == 0) return MC_OK;
+  if (key_offsets == nullptr || cache_offsets == nullptr) return MC_ERR_NULL;
+  if (key_offsets[0] < 0 || cache_offsets[0] < 0) return MC_ERR_SHAPE;
+  for (int32_t r = 0; r < batch; ++r) {
+    if (key_offsets[r + 1] < key_offsets[r]) return MC_ERR_SHAPE;
+    if (key_offsets[r + 1] - key_offsets[r] > INT32_MAX) return MC_ERR_RANGE;
+  }
+  for (int32_t i = 0; i < n_inst; ++i)
+    if (cache_offsets[i + 1] < cache_offsets[i]) return MC_ERR_SHAPE;
+  if (best_len == nullptr || best_inst == nullptr || (n_inst > 0 && prefix_len == nullptr)) return MC_ERR_NULL;
+  if ((key_offsets[batch] > key_offsets[0] && keys == nullptr) ||
+      (cache_offsets[n_inst] > cache_offsets[0] && cache_keys == nullptr))
+    return MC_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(keys) & 7u) || (reinterpret_cast<uintptr_t>(cache_keys) & 7u) ||
+      (reinterpret_cast<uintptr_t>(prefix_len) & 3u) || (reinterpret_cast<uintptr_t>(best_len) & 3u) ||
+      (reinterpret_cast<uintptr_t>(best_inst) & 3u) || (reinterpret_cast<uintptr_t>(workspace) & 15u))
+    return MC_ERR_ALIGN;
+  if (batch > 65535) return MC_ERR_RANGE;   // the match grid's second dimension
+  if (workspace == nullptr || workspace_bytes < mc_prefix_match_workspace_bytes(batch, n_inst)) return MC_ERR_WORKSPACE;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  const size_t n_tab = (size_t)batch + 1 + (size_t)n_inst + 1;
+  const size_t up = sizeof(int64_t) * n_tab;
+  int slot = -1;
+  int64_t* host = reinterpret_cast<int64_t*>(g_staging.acquire(up, &slot));
+  if (host == nullptr) return MC_ERR_HIP;
+  std::memcpy(host, key_offsets, sizeof(int64_t) * ((size_t)batch + 1));
+  std::memcpy(host + batch + 1, cache_offsets, sizeof(int64_t) * ((size_t)n_inst + 1));
+  if (hipMemcpyAsync(workspace, host, up, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
+  if (!g_staging.release_after(slot, stream)) return MC_ERR_HIP;
+  const int64_t* dev_tab = reinterpret_cast<const int64_t*>(workspace);
+  if (mc::launch_prefix_match(keys, dev_tab, batch, cache_keys, dev_tab + batch + 1, n_inst, prefix_len, best_len,
+                              best_inst, stream) != hipSuccess)
+    return MC_ERR_HIP;
+  return MC_OK;
+}
+
 }  // extern "C"

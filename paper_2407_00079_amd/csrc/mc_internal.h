@@ -66,4 +66,13 @@ hipError_t launch_kv_append(const void* k_new, const void* v_new, void* k_pool, 
                             const int32_t* block_tables, int32_t max_pages, const AttnReq* reqs, int32_t batch,
                             int64_t total_new, int32_t Hkv, hipStream_t stream);
 
+// enqueue digest + chain kernels: keys of total_blocks blocks (offset tables on the device)
+hipError_t launch_prefix_hash(const int32_t* tokens, const int64_t* tok_off, const int64_t* key_off, int batch,
+                              int block_tokens, int64_t total_blocks, uint64_t* keys, hipStream_t stream);
+
+// enqueue match + best kernels over batch requests and n_inst instances (offset tables on the device)
+hipError_t launch_prefix_match(const uint64_t* keys, const int64_t* key_off, int batch, const uint64_t* cache_keys,
+                               const int64_t* cache_off, int n_inst, int32_t* prefix_len, int32_t* best_len,
+                               int32_t* best_inst, hipStream_t stream);
+
 }  // namespace mc
