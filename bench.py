@@ -321,6 +321,53 @@ def main():
             "store_GBs_alone": round(layer_bytes / (ev[2].elapsed_time(ev[3]) / HL * 1e-3) / 1e9, 1),
             "bytes_per_layer_per_direction": layer_bytes}
         del kh_in, vh_in, kh_out, vh_out
+        # prefix keys of a batch of long prompts and their match against 16 instances' cache keys
+        NP, LP, BT, NI, NC = 64, 131072, 512, 16, 200000
+        g3 = torch.Generator(device=dev)
+        g3.manual_seed(20240707)
+        toks = torch.randint(0, 128000, (NP * LP,), dtype=torch.int32, device=dev, generator=g3)
+        toff = [i * LP for i in range(NP + 1)]
+        nkeys = NP * (LP // BT)
+        pkeys = torch.empty(nkeys, dtype=torch.int64, device=dev)
+        koff = [i * (LP // BT) for i in range(NP + 1)]
+        ws_h = torch.empty(B.mc_prefix_hash_workspace_bytes(NP), dtype=torch.uint8, device=dev)
+        ws_m = torch.empty(B.mc_prefix_match_workspace_bytes(NP, NI), dtype=torch.uint8, device=dev)
+        B.mc_prefix_hash(toks, toff, BT, pkeys, ws_h, s)
+        torch.cuda.synchronize()
+        # instance i holds NC random keys plus the first 16 (i + 1) keys of every request, ascending (uint64 order)
+        pk = pkeys.view(NP, LP // BT)
+        caches = []
+        for i in range(NI):
+            mine = torch.cat([torch.randint(-2 ** 62, 2 ** 62, (NC,), dtype=torch.int64, device=dev, generator=g3),
+                              pk[:, :16 * (i + 1)].reshape(-1)])
+            u = torch.unique(mine)
+            caches.append(torch.cat([u[u >= 0], u[u < 0]]))       # int64 bit patterns in unsigned ascending order
+        coff = [0]
+        for cch in caches:
+            coff.append(coff[-1] + cch.numel())
+        ckeys = torch.cat(caches)
+        plen = torch.empty((NP, NI), dtype=torch.int32, device=dev)
+        bl = torch.empty(NP, dtype=torch.int32, device=dev)
+        bi = torch.empty(NP, dtype=torch.int32, device=dev)
+        prefix = {"workload": f"{NP} prompts x {LP} tokens, {BT}-token blocks; {NI} instances of ~{NC + NP * 136} keys"}
+        for name, fn in (("hash", lambda: B.mc_prefix_hash(toks, toff, BT, pkeys, ws_h, s)),
+                         ("match", lambda: B.mc_prefix_match(pkeys, koff, ckeys, coff, plen, bl, bi, ws_m, s))):
+            for _ in range(3):
+                fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(s)
+            for _ in range(20):
+                fn()
+            b.record(s)
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / 20
+            prefix[name] = {"us": round(us, 1)}
+        prefix["hash"]["GBs"] = round(4 * NP * LP / (prefix["hash"]["us"] * 1e-6) / 1e9, 1)
+        prefix["hash"]["frac_hbm_peak"] = round(prefix["hash"]["GBs"] / HBM_PEAK_GBS, 4)
+        prefix["match"]["lookups_per_s"] = round(nkeys * NI / (prefix["match"]["us"] * 1e-6), 0)
+        prefix["match"]["best_len_of_request_0"] = int(bl[0].item())
+        result["prefix_keys"] = prefix
+        del toks, pkeys, ckeys, caches
         labels = {3: "config 3: 8/1 heads, P=122880, C=8192 (128k context)",
                   4: "config 4: 16 requests, 64/8 heads, prefixes U[0,32768] (page multiples), chunks lognormal(median 2048)"}
         del attn.q, attn.k, attn.v, attn.out, attn.k_new, attn.v_new
