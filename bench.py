@@ -147,7 +147,15 @@ def main():
 
     compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
 
+    # the order in which unpack takes the pages (ascending pool address): computed once per page list, as a caller
+    # would per request, and reused by every layer
+    order = torch.empty(n, dtype=torch.int32, device=dev)
+    B.mc_kv_page_order(dst_ids, n, order)
+
     def unpack(l, stream):
+        B.mc_kv_unpack_layer_ordered(k_remote[l], v_remote[l], N2, pb, dst_ids, order, n, k_pool[l], v_pool[l], stream)
+
+    def unpack_list_order(l, stream):
         B.mc_kv_unpack_layer(k_remote[l], v_remote[l], N2, pb, dst_ids, n, k_pool[l], v_pool[l], stream)
 
     def pack(l, stream):
@@ -228,7 +236,13 @@ def main():
                                    "tflops": round(attn.flops / (med * 1e-3) / 1e12, 2),
                                    "pct_mfma_peak": round(100 * attn.flops / (med * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2)}
         s = torch.cuda.current_stream()
-        for name, fn in (("pack", pack), ("unpack", unpack)):
+        def pack_ordered(l, stream):
+            B.mc_kv_pack_layer_ordered(k_pool[l], v_pool[l], N2, pb, dst_ids, order, n, k_store[l], v_store[l], stream)
+
+        # pack writes its output in list order, unpack (with the order) its pool pages in address order; the other
+        # two combinations are measured for comparison: the write side is the one that wants to be sequential
+        for name, fn in (("pack", pack), ("unpack", unpack), ("pack_pool_order", pack_ordered),
+                         ("unpack_list_order", unpack_list_order)):
             for l in range(LAY):
                 fn(l, s)
             reps = 80
@@ -240,10 +254,10 @@ def main():
             torch.cuda.synchronize()
             us = a.elapsed_time(b) * 1e3 / reps
             gbs = copy_bytes / (us * 1e-6) / 1e9
-            result[f"roofline_{name}"] = {"kernel": f"kv_copy_kernel<{name}>", "bound": "hbm", "achieved": round(gbs, 1),
+            result[f"roofline_{name}"] = {"kernel": f"kv_copy_kernel<{name.split('_')[0]}>", "bound": "hbm", "achieved": round(gbs, 1),
                                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                                           "us_per_layer": round(us, 2), "bytes_per_launch": copy_bytes,
-                                          "traffic": hbm(name)}
+                                          "traffic": hbm(name.split("_")[0])}
         # append of the step's chunk alone, launched back to back
         c = attn.case
         for _ in range(5):

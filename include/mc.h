@@ -208,6 +208,30 @@ mc_status mc_kv_unpack_layer(const void* k_in, const void* v_in, int64_t num_pag
                              void* k_pool_layer, void* v_pool_layer, void* hip_stream);
 
 /*
+ * The same two copies with the order in which the pages are taken chosen by the caller.  A
+ * request's page list is the same for all layers, so it pays to compute once
+ *
+ *   order[r] = the position in page_ids of the r-th smallest page id (equal ids: lower position
+ *              first) - what mc_kv_page_order writes -
+ *
+ * and hand it to every layer's pack / unpack: the scattered side of the copy then walks the pool
+ * in ascending address order, which the HBM sustains at a higher rate than a random walk.  The
+ * bytes moved and where they land are exactly those of mc_kv_pack_layer / mc_kv_unpack_layer;
+ * `order` must be a permutation of 0 .. n-1 (not checked: entries outside that range are
+ * undefined behaviour, a repeated entry leaves pages uncopied), or NULL for list order.
+ *
+ *   order  dev  int32 [n]
+ * mc_kv_page_order costs O(n^2 / threads) and rejects n > 2^20 with MC_ERR_RANGE.
+ */
+mc_status mc_kv_page_order(const int32_t* page_ids, int64_t n, int32_t* order, void* hip_stream);
+mc_status mc_kv_pack_layer_ordered(const void* k_pool_layer, const void* v_pool_layer, int64_t num_pages,
+                                   int64_t page_bytes, const int32_t* page_ids, const int32_t* order,
+                                   int64_t n, void* k_out, void* v_out, void* hip_stream);
+mc_status mc_kv_unpack_layer_ordered(const void* k_in, const void* v_in, int64_t num_pages,
+                                     int64_t page_bytes, const int32_t* page_ids, const int32_t* order,
+                                     int64_t n, void* k_pool_layer, void* v_pool_layer, void* hip_stream);
+
+/*
  * Layer-wise prefill against the CPU-DRAM KVCache pool (Section 5.2: a layer's KVCache is loaded
  * before its attention and stored after it, asynchronously; Section 3 steps 1 and 3: the prefix
  * comes from, and the new KVCache goes back to, host memory).  One layer, one direction, all on

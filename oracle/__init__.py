@@ -257,3 +257,10 @@ def prefix_match(keys, key_offsets, cache_keys, cache_offsets):
     if rc != 0:
         raise ValueError("oracle rejected its arguments")
     return plen, best_len, best_inst
+
+
+def kv_page_order(page_ids) -> np.ndarray:
+    """order[r] = position in ``page_ids`` of the r-th smallest id, equal ids in list order: the stable
+    ascending sort of the positions, by the library's stable argsort."""
+    ids = np.ascontiguousarray(page_ids, dtype=np.int32)
+    return np.argsort(ids, kind="stable").astype(np.int32)

@@ -22,7 +22,8 @@ EXPORTS = ("mc_status_string", "mc_prefill_attn_workspace_bytes", "mc_prefill_at
            "mc_kv_pack_layer", "mc_kv_unpack_layer", "mc_kv_append_workspace_bytes", "mc_kv_append_paged",
            "mc_prefill_attn_split_workspace_bytes", "mc_prefill_attn_paged_split", "mc_attn_merge_lse",
            "mc_kv_load_layer", "mc_kv_store_layer", "mc_prefix_hash_workspace_bytes", "mc_prefix_hash",
-           "mc_prefix_match_workspace_bytes", "mc_prefix_match")
+           "mc_prefix_match_workspace_bytes", "mc_prefix_match", "mc_kv_page_order", "mc_kv_pack_layer_ordered",
+           "mc_kv_unpack_layer_ordered")
 MC_MAX_KV_SPLITS = 256
 
 
@@ -64,6 +65,11 @@ def lib():
         for f in (l.mc_kv_pack_layer, l.mc_kv_unpack_layer):
             f.restype = ctypes.c_int
             f.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, vp]
+        l.mc_kv_page_order.restype = ctypes.c_int
+        l.mc_kv_page_order.argtypes = [vp, i64, vp, vp]
+        for f in (l.mc_kv_pack_layer_ordered, l.mc_kv_unpack_layer_ordered):
+            f.restype = ctypes.c_int
+            f.argtypes = [vp, vp, i64, i64, vp, vp, i64, vp, vp, vp]
         l.mc_kv_append_workspace_bytes.restype = ctypes.c_size_t
         l.mc_kv_append_workspace_bytes.argtypes = [i32]
         l.mc_kv_append_paged.restype = ctypes.c_int
@@ -204,6 +210,31 @@ def mc_kv_unpack_layer(k_in, v_in, num_pages: int, page_bytes: int, page_ids, n:
                                 _dev_ptr(k_pool_layer), _dev_ptr(v_pool_layer), _stream_handle(stream))
     if st != MC_OK:
         raise McError(st, "mc_kv_unpack_layer")
+
+
+def mc_kv_page_order(page_ids, n: int, order, stream=None) -> None:
+    """Enqueue order[r] = position of the r-th smallest page id (int32 device tensors)."""
+    st = int(lib().mc_kv_page_order(_dev_ptr(page_ids), n, _dev_ptr(order), _stream_handle(stream)))
+    if st != MC_OK:
+        raise McError(st, "mc_kv_page_order")
+
+
+def mc_kv_pack_layer_ordered(k_pool_layer, v_pool_layer, num_pages: int, page_bytes: int, page_ids, order, n: int,
+                             k_out, v_out, stream=None) -> None:
+    st = int(lib().mc_kv_pack_layer_ordered(_dev_ptr(k_pool_layer), _dev_ptr(v_pool_layer), num_pages, page_bytes,
+                                            _dev_ptr(page_ids), _dev_ptr(order), n, _dev_ptr(k_out), _dev_ptr(v_out),
+                                            _stream_handle(stream)))
+    if st != MC_OK:
+        raise McError(st, "mc_kv_pack_layer_ordered")
+
+
+def mc_kv_unpack_layer_ordered(k_in, v_in, num_pages: int, page_bytes: int, page_ids, order, n: int, k_pool_layer,
+                               v_pool_layer, stream=None) -> None:
+    st = int(lib().mc_kv_unpack_layer_ordered(_dev_ptr(k_in), _dev_ptr(v_in), num_pages, page_bytes,
+                                              _dev_ptr(page_ids), _dev_ptr(order), n, _dev_ptr(k_pool_layer),
+                                              _dev_ptr(v_pool_layer), _stream_handle(stream)))
+    if st != MC_OK:
+        raise McError(st, "mc_kv_unpack_layer_ordered")
 
 
 def mc_kv_load_layer_raw(k_host, v_host, k_stage, v_stage, num_pages, page_bytes, page_ids, n, k_pool, v_pool,

@@ -378,27 +378,53 @@ static mc_status check_copy(const void* a, const void* b, int64_t num_pages, int
   return MC_OK;
 }
 
-mc_status mc_kv_pack_layer(const void* k_pool_layer, const void* v_pool_layer, int64_t num_pages, int64_t page_bytes,
-                           const int32_t* page_ids, int64_t n, void* k_out, void* v_out, void* hip_stream) {
+mc_status mc_kv_page_order(const int32_t* page_ids, int64_t n, int32_t* order, void* hip_stream) {
+  if (n < 0) return MC_ERR_SHAPE;
+  if (n == 0) return MC_OK;
+  if (page_ids == nullptr || order == nullptr) return MC_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(page_ids) & 3u) || (reinterpret_cast<uintptr_t>(order) & 3u)) return MC_ERR_ALIGN;
+  if (n > (int64_t)1 << 20) return MC_ERR_RANGE;   // quadratic in n: a request's page list, not a pool
+  if (mc::launch_kv_page_order(page_ids, n, order, reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return MC_ERR_HIP;
+  return MC_OK;
+}
+
+mc_status mc_kv_pack_layer_ordered(const void* k_pool_layer, const void* v_pool_layer, int64_t num_pages,
+                                   int64_t page_bytes, const int32_t* page_ids, const int32_t* order, int64_t n,
+                                   void* k_out, void* v_out, void* hip_stream) {
   mc_status st = check_copy(k_pool_layer, v_pool_layer, num_pages, page_bytes, page_ids, n, k_out, v_out);
   if (st != MC_OK || n == 0 || page_bytes == 0) return st;
-  if (mc::launch_kv_copy(true, k_pool_layer, v_pool_layer, k_out, v_out, page_ids, n, page_bytes,
+  if (reinterpret_cast<uintptr_t>(order) & 3u) return MC_ERR_ALIGN;
+  if (mc::launch_kv_copy(true, k_pool_layer, v_pool_layer, k_out, v_out, page_ids, order, n, page_bytes,
                          reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return MC_ERR_HIP;
   return MC_OK;
+}
+
+mc_status mc_kv_unpack_layer_ordered(const void* k_in, const void* v_in, int64_t num_pages, int64_t page_bytes,
+                                     const int32_t* page_ids, const int32_t* order, int64_t n, void* k_pool_layer,
+                                     void* v_pool_layer, void* hip_stream) {
+  mc_status st = check_copy(k_in, v_in, num_pages, page_bytes, page_ids, n, k_pool_layer, v_pool_layer);
+  if (st != MC_OK || n == 0 || page_bytes == 0) return st;
+  if (reinterpret_cast<uintptr_t>(order) & 3u) return MC_ERR_ALIGN;
+  if (mc::launch_kv_copy(false, k_in, v_in, k_pool_layer, v_pool_layer, page_ids, order, n, page_bytes,
+                         reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return MC_ERR_HIP;
+  return MC_OK;
+}
+
+mc_status mc_kv_pack_layer(const void* k_pool_layer, const void* v_pool_layer, int64_t num_pages, int64_t page_bytes,
+                           const int32_t* page_ids, int64_t n, void* k_out, void* v_out, void* hip_stream) {
+  return mc_kv_pack_layer_ordered(k_pool_layer, v_pool_layer, num_pages, page_bytes, page_ids, nullptr, n, k_out,
+                                  v_out, hip_stream);
 }
 
 mc_status mc_kv_unpack_layer(const void* k_in, const void* v_in, int64_t num_pages, int64_t page_bytes,
                              const int32_t* page_ids, int64_t n, void* k_pool_layer, void* v_pool_layer,
                              void* hip_stream) {
-  mc_status st = check_copy(k_in, v_in, num_pages, page_bytes, page_ids, n, k_pool_layer, v_pool_layer);
-  if (st != MC_OK || n == 0 || page_bytes == 0) return st;
-  if (mc::launch_kv_copy(false, k_in, v_in, k_pool_layer, v_pool_layer, page_ids, n, page_bytes,
-                         reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
-    return MC_ERR_HIP;
-  return MC_OK;
+  return mc_kv_unpack_layer_ordered(k_in, v_in, num_pages, page_bytes, page_ids, nullptr, n, k_pool_layer,
+                                    v_pool_layer, hip_stream);
 }
-
 
 mc_status mc_kv_load_layer(const void* k_host, const void* v_host, void* k_stage, void* v_stage, int64_t num_pages,
                            int64_t page_bytes, const int32_t* page_ids, int64_t n, void* k_pool_layer,
@@ -411,7 +437,7 @@ mc_status mc_kv_load_layer(const void* k_host, const void* v_host, void* k_stage
   const size_t bytes = (size_t)n * (size_t)page_bytes;
   if (hipMemcpyAsync(k_stage, k_host, bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
   if (hipMemcpyAsync(v_stage, v_host, bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
-  if (mc::launch_kv_copy(false, k_stage, v_stage, k_pool_layer, v_pool_layer, page_ids, n, page_bytes, stream) !=
+  if (mc::launch_kv_copy(false, k_stage, v_stage, k_pool_layer, v_pool_layer, page_ids, nullptr, n, page_bytes, stream) !=
       hipSuccess)
     return MC_ERR_HIP;
   return MC_OK;
@@ -426,7 +452,7 @@ mc_status mc_kv_store_layer(const void* k_pool_layer, const void* v_pool_layer, 
   if (!aligned16(k_host) || !aligned16(v_host)) return MC_ERR_ALIGN;
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   const size_t bytes = (size_t)n * (size_t)page_bytes;
-  if (mc::launch_kv_copy(true, k_pool_layer, v_pool_layer, k_stage, v_stage, page_ids, n, page_bytes, stream) !=
+  if (mc::launch_kv_copy(true, k_pool_layer, v_pool_layer, k_stage, v_stage, page_ids, nullptr, n, page_bytes, stream) !=
       hipSuccess)
     return MC_ERR_HIP;
   if (hipMemcpyAsync(k_host, k_stage, bytes, hipMemcpyDeviceToHost, stream) != hipSuccess) return MC_ERR_HIP;

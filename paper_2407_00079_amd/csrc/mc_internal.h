@@ -57,9 +57,14 @@ hipError_t launch_attn_merge(int dtype, const float* o_parts, const float* lse_p
 // 16-byte vectors of a page one copy workgroup moves (host needs it for the grid-size range check)
 int kv_copy_slice_vecs();
 
-// enqueue gather (pack) or scatter (unpack) of n pages of page_bytes for K and V
+// enqueue gather (pack) or scatter (unpack) of n pages of page_bytes for K and V; `order` (or null)
+// lists the positions of page_ids in the order the workgroups should take them
 hipError_t launch_kv_copy(bool pack, const void* k_src, const void* v_src, void* k_dst, void* v_dst,
-                          const int32_t* page_ids, int64_t n, int64_t page_bytes, hipStream_t stream);
+                          const int32_t* page_ids, const int32_t* order, int64_t n, int64_t page_bytes,
+                          hipStream_t stream);
+
+// enqueue the computation of order[r] = position of the r-th smallest page id (stable)
+hipError_t launch_kv_page_order(const int32_t* page_ids, int64_t n, int32_t* order, hipStream_t stream);
 
 // enqueue the scatter of total_new tokens' K/V rows (256 bytes per KV head) into their page slots
 hipError_t launch_kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,

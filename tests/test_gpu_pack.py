@@ -89,3 +89,47 @@ def test_round_trip_at_full_layer_size_on_a_side_stream(oracle):
 def test_empty_list_is_a_noop():
     B.mc_kv_pack_layer(None, None, 8, 4096, None, 0, None, None)
     B.mc_kv_unpack_layer(None, None, 8, 4096, None, 0, None, None)
+
+
+@pytest.mark.parametrize("n,N,unique", [(300, 512, True), (1, 4, True), (2048, 4096, True), (1500, 40, False),
+                                        (1025, 5000, True)])
+def test_page_order_matches_oracle(oracle, n, N, unique):
+    rng = np.random.default_rng(n)
+    ids = (rng.permutation(N)[:n] if unique else rng.integers(0, N, size=n)).astype(np.int32)
+    order = torch.full((n,), -1, dtype=torch.int32, device="cuda:0")
+    B.mc_kv_page_order(_dev(ids), n, order)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(order.cpu().numpy(), oracle.kv_page_order(ids))
+
+
+@pytest.mark.parametrize("page_bytes,n,N", [(32768, 300, 512), (16400, 37, 64), (4096, 24, 64)])
+def test_ordered_copies_move_the_same_bytes(oracle, page_bytes, n, N):
+    pc = W.make_pack_case(99 + n, 1, N, N, page_bytes, n)
+    rng = np.random.default_rng(n)
+    for which in ("sorted", "arbitrary"):
+        print(f"ordered copy page_bytes={page_bytes} n={n} order={which}", flush=True)
+        kp, vp = _dev(pc.k_pools[0]), _dev(pc.v_pools[0])
+        src, dst = _dev(pc.src_ids), _dev(pc.dst_ids)
+        o_src = torch.empty(n, dtype=torch.int32, device="cuda:0")
+        o_dst = torch.empty(n, dtype=torch.int32, device="cuda:0")
+        if which == "sorted":
+            B.mc_kv_page_order(src, n, o_src)
+            B.mc_kv_page_order(dst, n, o_dst)
+        else:
+            o_src.copy_(torch.from_numpy(rng.permutation(n).astype(np.int32)))
+            o_dst.copy_(torch.from_numpy(rng.permutation(n).astype(np.int32)))
+        k_out = torch.zeros((n, page_bytes), dtype=torch.uint8, device="cuda:0")
+        v_out = torch.zeros_like(k_out)
+        B.mc_kv_pack_layer_ordered(kp, vp, N, page_bytes, src, o_src, n, k_out, v_out)
+        k_ref, v_ref = oracle.kv_pack_layer(pc.k_pools[0], pc.v_pools[0], pc.src_ids)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(k_out.cpu().numpy(), k_ref)
+        np.testing.assert_array_equal(v_out.cpu().numpy(), v_ref)
+        k2_host = rng.integers(0, 256, size=(N, page_bytes), dtype=np.uint8)
+        v2_host = rng.integers(0, 256, size=(N, page_bytes), dtype=np.uint8)
+        k2, v2 = _dev(k2_host), _dev(v2_host)
+        B.mc_kv_unpack_layer_ordered(k_out, v_out, N, page_bytes, dst, o_dst, n, k2, v2)
+        oracle.kv_unpack_layer(k_ref, v_ref, pc.dst_ids, k2_host, v2_host)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(k2.cpu().numpy(), k2_host)
+        np.testing.assert_array_equal(v2.cpu().numpy(), v2_host)

@@ -92,3 +92,13 @@ def test_empty_list(oracle):
     pc = W.make_pack_case(8, layers=1, num_pages=8, num_pages_dst=8, page_bytes=64, n=0)
     k_out, v_out = oracle.kv_pack_layer(pc.k_pools[0], pc.v_pools[0], pc.src_ids)
     assert k_out.shape == (0, 64) and v_out.shape == (0, 64)
+
+
+def test_page_order_is_the_stable_ascending_permutation(oracle):
+    rng = np.random.default_rng(12)
+    for ids in (rng.permutation(50)[:20], rng.integers(0, 6, size=40), np.array([], dtype=np.int32), np.array([7])):
+        order = oracle.kv_page_order(ids)
+        n = len(ids)
+        assert sorted(order.tolist()) == list(range(n))                       # a permutation of the positions
+        for a, b in zip(order[:-1], order[1:]):                                # by definition, pair by pair
+            assert ids[a] < ids[b] or (ids[a] == ids[b] and a < b)
