@@ -205,7 +205,7 @@ def main():
 
     def hbm(prefix):
         r, w = traffic.get(prefix + "_read_bytes"), traffic.get(prefix + "_write_bytes")
-        return None if r is None or w is None else {"read_bytes": r, "write_bytes": w, "unit": "B per launch",
+        return None if r is None or w is None else {"bytes": r + w, "read_bytes": r, "write_bytes": w, "unit": "B per launch",
                                                     "source": "profiles/hbm_traffic_bench_step.txt"}
 
     result = {

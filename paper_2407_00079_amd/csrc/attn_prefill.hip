@@ -82,6 +82,11 @@ __device__ __forceinline__ float sum_with_other_half(float x) {
 // know LDS is being written behind its back: it would otherwise make the first LDS read
 // after the copy wait for the copy (vmcnt), which is exactly what the tile pipeline avoids.
 // Ordering is the kernel's own business: s_waitcnt vmcnt(0) + barrier before a tile is read.
+// (M0 is a register the compiler reserves for itself; it sets it right before each of its own
+// uses and has none in this kernel, so naming it as clobbered is all that is needed - the
+// diagnostic about reserved registers in a clobber list is expected here.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16(const char* sbase, uint32_t voff, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
                :: "s"(sbase), "v"(voff), "s"(lds_base) : "m0", "memory");
@@ -90,6 +95,7 @@ __device__ __forceinline__ void dma16(const char* vaddr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :: "v"(vaddr), "s"(lds_base) : "m0", "memory");
 }
+#pragma clang diagnostic pop
 
 // ---------------------------------------------------------------------------
 // dtype traits: how fragments are fetched and multiplied
@@ -137,8 +143,8 @@ struct Bf16 {
   }
   static __device__ __forceinline__ frag load_v(uint32_t vt_lane, int kb, int step, int db) {
     const uint32_t p = (vt_lane ^ (uint32_t)(db << 6)) + (kb * 32 + step * 16) * kRowBytes;
-    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(p));
-    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(p + 8 * kRowBytes));
+    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(uintptr_t)(p));
+    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(uintptr_t)(p + 8 * kRowBytes));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   }
   // A block's probabilities as P V multiplies them: rounded to bf16, fragment `step` holds the
@@ -253,7 +259,6 @@ struct F32 {
 template <class T, int WAVES, bool SPLIT>
 __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) char smem[3 * kStageBytes];   // three (K, V) tiles
-  constexpr int kThreads = WAVES * 64;
   constexpr int kTileRows = WAVES * 32;
 
   const int tid = threadIdx.x;
