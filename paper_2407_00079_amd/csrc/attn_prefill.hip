@@ -44,6 +44,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #ifndef MC_WAVES
 #define MC_WAVES 8
 #endif
+#ifndef MC_SKEW
+#define MC_SKEW 1
+#endif
 
 constexpr int kTileKeys = 64;          // keys per LDS tile = 4 pages of 16
 constexpr int kPageTokens = 16;
@@ -499,17 +502,15 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   // the tile still in LDS, the reference is raised to their true maximum and the probabilities
   // are redone; nothing has been accumulated from the discarded ones.
   constexpr float kSumGuard = 4096.0f;   // 16 probabilities of at most 2^kRescaleSlack each
-  // step(block j = (buf_cur, kb_cur); block j+2 = (buf_pre, kb_pre))
-  auto step = [&](int buf_cur, int kb_cur, int buf_pre, int kb_pre) __attribute__((always_inline)) {
+  // block j = (buf_cur, kb_cur); block j+2 = (buf_pre, kb_pre)
+  typename T::pblock pb;
+  auto phase_a = [&](int buf_cur, int kb_cur) __attribute__((always_inline)) {
     const uint32_t vt = v_lane + buf_cur * kStageBytes;
-    const uint32_t kt = k_lane + buf_pre * kStageBytes;
     s_cur = s_next;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s_next[r] = 0.f;
-    typename T::pblock pb;
     float bsum = 0.f;
     const float m_ref = SPLIT ? fmaxf(m_run, kNoKeyYet) : m_run;
-    // ---- phase A
 #pragma unroll
     for (int i = 0; i < kRing; ++i) {
       s_next = T::mma(ring[i], qf[i], s_next);
@@ -530,7 +531,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
       bsum = probabilities(s_cur, pb);
     }
     l_sum += bsum;
-    // ---- phase B
+  };
+  auto phase_b = [&](int buf_pre, int kb_pre) __attribute__((always_inline)) {
+    const uint32_t kt = k_lane + buf_pre * kStageBytes;
 #pragma unroll
     for (int i = 0; i < kRing; ++i) {
       o[i % T::kDBlocks] = T::mma(ring[i], T::p_frag(pb, i / T::kDBlocks), o[i % T::kDBlocks]);
@@ -584,11 +587,22 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   if (tile < n_plain) {
     settle_reference(s_next, 0, std::false_type{});
     load_k_ring(0, 1);
+    // The two waves of a SIMD run half a step apart: the second one (waves WAVES/2 ..) passes the
+    // tile barrier between the two phases of the tile's first step instead of before it.  When
+    // the barrier opens one wave of each SIMD starts a phase A (a dependent MFMA chain under
+    // heavy vector work) and the other a phase B (independent MFMAs, no vector work), so the
+    // matrix pipe always has an MFMA that is ready and the vector ALU is never wanted twice.
+    // Safe because phase A of a tile's first step reads nothing of the tile before it and
+    // nothing of the tile after it, and every wave still passes one barrier per tile.
+    const bool late_barrier = MC_SKEW && wave_u >= WAVES / 2;
     for (; tile < n_plain; ++tile) {
       const int buf_next = buf == 2 ? 0 : buf + 1;
-      tile_sync(tile);
-      step(buf, 0, buf_next, 0);   // block 0: scores of block 1, then the K fragments of the next tile's block 0
-      step(buf, 1, buf_next, 1);   // block 1: scores of the next tile's block 0, then the K fragments of its block 1
+      if (!late_barrier) tile_sync(tile);
+      phase_a(buf, 0);             // block 0: scores of block 1 ...
+      if (late_barrier) tile_sync(tile);
+      phase_b(buf_next, 0);        // ... then the K fragments of the next tile's block 0
+      phase_a(buf, 1);             // block 1: scores of the next tile's block 0 ...
+      phase_b(buf_next, 1);        // ... then the K fragments of its block 1
       buf = buf_next;
     }
   }
