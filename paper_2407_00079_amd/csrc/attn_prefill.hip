@@ -54,7 +54,11 @@ constexpr int kRowBytes = 256;         // one K or V row: 128 bf16 or 64 f32
 constexpr int kPageHeadBytes = kPageTokens * kRowBytes;   // 4 KiB, contiguous in the pool
 constexpr int kKTileBytes = kTileKeys * kRowBytes;        // 16 KiB; rows dense, granules swizzled
 constexpr int kVTileBytes = kTileKeys * kRowBytes;
-constexpr int kStageBytes = kKTileBytes + kVTileBytes;    // a multiple of 32 KiB: XOR constants (< 256) never touch it
+constexpr int kBuffers = 3;
+// LDS: the K tiles of the three buffers, then the V tiles.  Every tile starts at a multiple of
+// 16 KiB, so the XOR constants of the swizzle (< 256) never reach a tile base, and the offset of
+// any fragment from its lane's base register stays below the 64 KiB a ds_read immediate can hold.
+constexpr int kVBase = kBuffers * kKTileBytes;
 constexpr float kRescaleSlack = 8.0f;  // log2 units the running max may lag behind
 // stands in for a reference of -inf when probabilities are formed: masked scores (-inf) then give
 // exp2(-inf) = 0 instead of exp2(-inf + inf) = NaN; a row with a finite score has a finite reference
@@ -128,9 +132,11 @@ struct Bf16 {
     const int r = lane & 31, h = lane >> 5;
     return r * kRowBytes + (((r >> 1) & 7) << 5) + ((h ^ (r & 1)) << 4);
   }
-  // A operand: K[32*kb + lane%32][16*kk + 8*half .. +7]
-  static __device__ __forceinline__ frag load_k(uint32_t kt_lane, int kb, int kk) {
-    return *reinterpret_cast<MC_LDS const frag*>((kt_lane ^ (uint32_t)(kk << 5)) + kb * 32 * kRowBytes);
+  // A operand: K[32*kb + lane%32][16*kk + 8*half .. +7]; kx[kk] = lane base ^ (kk << 5), off = tile + block offset
+  static constexpr int kKX = kQKSteps;
+  static __device__ __forceinline__ uint32_t k_xor(int i) { return (uint32_t)(i << 5); }
+  static __device__ __forceinline__ frag load_k(const uint32_t (&kx)[kKX], int off, int kk) {
+    return *reinterpret_cast<MC_LDS const frag*>(kx[kk] + off);
   }
   // A operand of O^T += V^T P^T: V[key(e)][db*32 + lane%32] for the 8 keys
   // 32*kb + 16*step + 8*(e/4) + 4*half + e%4, i.e. two groups of 4 consecutive keys.
@@ -144,8 +150,11 @@ struct Bf16 {
     const int col_bytes = (((lane >> 4) & 1) * 16 + (s & 3) * 4) * 2;   // < 64
     return r * kRowBytes + ((r & 3) << 6) + col_bytes;
   }
-  static __device__ __forceinline__ frag load_v(uint32_t vt_lane, int kb, int step, int db) {
-    const uint32_t p = (vt_lane ^ (uint32_t)(db << 6)) + (kb * 32 + step * 16) * kRowBytes;
+  static constexpr int kVX = kDBlocks;
+  static __device__ __forceinline__ uint32_t v_xor(int i) { return (uint32_t)(i << 6); }
+  // vx[db] = lane base ^ (db << 6), off = tile + block offset
+  static __device__ __forceinline__ frag load_v(const uint32_t (&vx)[kVX], int off, int step, int db) {
+    const uint32_t p = vx[db] + off + step * 16 * kRowBytes;
     bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(uintptr_t)(p));
     bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(uintptr_t)(p + 8 * kRowBytes));
     return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -220,16 +229,18 @@ struct F32 {
     const int r = lane & 31;
     return r * kRowBytes + ((r & 15) << 4) + (lane >> 5) * 4;
   }
-  // A operand: K[32*kb + lane%32][2*kk + half]
-  static __device__ __forceinline__ frag load_k(uint32_t kt_lane, int kb, int kk) {
-    return *reinterpret_cast<MC_LDS const float*>((kt_lane ^ (uint32_t)((kk >> 1) << 4)) + (kk & 1) * 8 +
-                                                  kb * 32 * kRowBytes);
+  // A operand: K[32*kb + lane%32][2*kk + half]; kx[kk/2] = lane base ^ ((kk/2) << 4)
+  static constexpr int kKX = kQKSteps / 2;
+  static __device__ __forceinline__ uint32_t k_xor(int i) { return (uint32_t)(i << 4); }
+  static __device__ __forceinline__ frag load_k(const uint32_t (&kx)[kKX], int off, int kk) {
+    return *reinterpret_cast<MC_LDS const float*>(kx[kk >> 1] + (kk & 1) * 8 + off);
   }
   // step = accumulator register r: key 32*kb + 8*(r/4) + 4*half + r%4, column db*32 + lane%32
   static __device__ __forceinline__ int v_lane_off(int lane) { return (lane >> 5) * 4 * kRowBytes + (lane & 31) * 4; }
-  static __device__ __forceinline__ frag load_v(uint32_t vt_lane, int kb, int step, int db) {
-    return *reinterpret_cast<MC_LDS const float*>(vt_lane + (kb * 32 + (step >> 2) * 8 + (step & 3)) * kRowBytes +
-                                                  db * 128);
+  static constexpr int kVX = 1;
+  static __device__ __forceinline__ uint32_t v_xor(int) { return 0; }
+  static __device__ __forceinline__ frag load_v(const uint32_t (&vx)[kVX], int off, int step, int db) {
+    return *reinterpret_cast<MC_LDS const float*>(vx[0] + off + ((step >> 2) * 8 + (step & 3)) * kRowBytes + db * 128);
   }
   struct pblock { f32x16 p; };
   static __device__ __forceinline__ pblock round_p(const f32x16& p) { return pblock{p}; }
@@ -261,7 +272,7 @@ struct F32 {
 // mc_attn_merge_lse to combine (paper Section 5.1: attention is associative over key slices).
 template <class T, int WAVES, bool SPLIT>
 __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) char smem[3 * kStageBytes];   // three (K, V) tiles
+  __shared__ __attribute__((aligned(16))) char smem[kBuffers * (kKTileBytes + kVTileBytes)];
   constexpr int kTileRows = WAVES * 32;
 
   const int tid = threadIdx.x;
@@ -368,7 +379,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   // enqueue the copy of tile `tile` (page ids in pid[]) into LDS buffer `buf`
   auto fetch = [&](int tile, int buf) __attribute__((always_inline)) {
     if (!fetcher) return;
-    const uint32_t dst0 = smem_base + buf * kStageBytes + wave_u * 1024;
+    const uint32_t dst0 = smem_base + buf * kKTileBytes + wave_u * 1024;
     if ((tile + 1) * kTileKeys <= L) {
       // whole tile inside the sequence: scalar page base + constant lane offset
 #pragma unroll
@@ -376,7 +387,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
         const int64_t page_off = (int64_t)pid[i] * page_stride;
         const uint32_t dst = dst0 + i * kFetchWaves * 1024;
         dma16(kbase + page_off, k_src, dst);
-        dma16(vbase + page_off, v_src, dst + kKTileBytes);
+        dma16(vbase + page_off, v_src, dst + kVBase);
       }
     } else {
       // Slots at or past the request's length may hold anything (NaN would survive p = 0 in P V):
@@ -390,7 +401,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
         const char* vs = vbase + (in_seq ? page_off + v_src : first_page_off + (v_src & 255));
         const uint32_t dst = dst0 + i * kFetchWaves * 1024;
         dma16(ks, dst);
-        dma16(vs, dst + kKTileBytes);
+        dma16(vs, dst + kVBase);
       }
     }
   };
@@ -407,18 +418,25 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
     for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   const float c = a.scale_log2e;
   const uint32_t k_lane = smem_base + T::k_lane_off(lane);
-  const uint32_t v_lane = smem_base + kKTileBytes + T::v_lane_off(lane);
+  const uint32_t v_lane = smem_base + kVBase + T::v_lane_off(lane);
+  // lane bases with the swizzle's XOR already applied: a fragment address is one of these plus a
+  // constant, and in the pipeline (buffer known at compile time) that constant is an immediate
+  uint32_t kx[T::kKX], vx[T::kVX];
+#pragma unroll
+  for (int i = 0; i < T::kKX; ++i) kx[i] = k_lane ^ T::k_xor(i);
+#pragma unroll
+  for (int i = 0; i < T::kVX; ++i) vx[i] = v_lane ^ T::v_xor(i);
 
   // ---- building blocks that are NOT on the steady-state path (prologue, last block, rare recompute)
   // S^T block = K Q^T for keys [32*kb, 32*kb+32) of the tile in LDS buffer `buf`, one K fragment
   // in flight at a time (it runs where registers are scarce)
   auto qk_block = [&](int buf, int kb, f32x16& s) __attribute__((always_inline)) {
-    const uint32_t kt = k_lane + buf * kStageBytes;
+    const int off = buf * kKTileBytes + kb * 32 * kRowBytes;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < T::kQKSteps; ++kk) {
-      const typename T::frag kf = T::load_k(kt, kb, kk);
+      const typename T::frag kf = T::load_k(kx, off, kk);
       s = T::mma(kf, qf[kk], s);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -463,11 +481,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   };
   // O^T += V^T P^T for the block's 32 keys, V fragments read just in time
   auto pv_block = [&](int buf, int kb, const typename T::pblock& pb) __attribute__((always_inline)) {
-    const uint32_t vt = v_lane + buf * kStageBytes;
+    const int off = buf * kVTileBytes + kb * 32 * kRowBytes;
 #pragma unroll
     for (int st = 0; st < T::kPVSteps; ++st)
 #pragma unroll
-      for (int db = 0; db < T::kDBlocks; ++db) o[db] = T::mma(T::load_v(vt, kb, st, db), T::p_frag(pb, st), o[db]);
+      for (int db = 0; db < T::kDBlocks; ++db) o[db] = T::mma(T::load_v(vx, off, st, db), T::p_frag(pb, st), o[db]);
   };
 
   // ---- KV loop.  Software pipeline over 32-key blocks, scheduled by hand: the order written
@@ -490,9 +508,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   typename T::frag ring[kRing];
   f32x16 s_cur, s_next;
   auto load_k_ring = [&](int buf, int kb) __attribute__((always_inline)) {
-    const uint32_t kt = k_lane + buf * kStageBytes;
+    const int off = buf * kKTileBytes + kb * 32 * kRowBytes;
 #pragma unroll
-    for (int i = 0; i < kRing; ++i) ring[i] = T::load_k(kt, kb, i);
+    for (int i = 0; i < kRing; ++i) ring[i] = T::load_k(kx, off, i);
   };
 
   // The pipeline only ever sees fully visible blocks, and it takes no maxima.  Probabilities are formed
@@ -505,7 +523,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   // block j = (buf_cur, kb_cur); block j+2 = (buf_pre, kb_pre)
   typename T::pblock pb;
   auto phase_a = [&](int buf_cur, int kb_cur) __attribute__((always_inline)) {
-    const uint32_t vt = v_lane + buf_cur * kStageBytes;
+    const int off_v = buf_cur * kVTileBytes + kb_cur * 32 * kRowBytes;
     s_cur = s_next;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s_next[r] = 0.f;
@@ -514,7 +532,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
 #pragma unroll
     for (int i = 0; i < kRing; ++i) {
       s_next = T::mma(ring[i], qf[i], s_next);
-      ring[i] = T::load_v(vt, kb_cur, i / T::kDBlocks, i % T::kDBlocks);
+      ring[i] = T::load_v(vx, off_v, i / T::kDBlocks, i % T::kDBlocks);
       if (i % kEvery == 0) {
         const int e0 = i / kEvery * kPer;
 #pragma unroll
@@ -533,11 +551,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
     l_sum += bsum;
   };
   auto phase_b = [&](int buf_pre, int kb_pre) __attribute__((always_inline)) {
-    const uint32_t kt = k_lane + buf_pre * kStageBytes;
+    const int off_k = buf_pre * kKTileBytes + kb_pre * 32 * kRowBytes;
 #pragma unroll
     for (int i = 0; i < kRing; ++i) {
       o[i % T::kDBlocks] = T::mma(ring[i], T::p_frag(pb, i / T::kDBlocks), o[i % T::kDBlocks]);
-      ring[i] = T::load_k(kt, kb_pre, i);
+      ring[i] = T::load_k(kx, off_k, i);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -595,15 +613,27 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
     // Safe because phase A of a tile's first step reads nothing of the tile before it and
     // nothing of the tile after it, and every wave still passes one barrier per tile.
     const bool late_barrier = MC_SKEW && wave_u >= WAVES / 2;
-    for (; tile < n_plain; ++tile) {
-      const int buf_next = buf == 2 ? 0 : buf + 1;
+    // The loop body is written out for the three buffers in turn, so that inside it every tile
+    // offset is a compile-time constant and goes into the LDS instructions' immediate fields.
+    auto pipelined_tile = [&](auto buf_tag) __attribute__((always_inline)) {
+      constexpr int b = decltype(buf_tag)::value, bn = (b + 1) % kBuffers;
+      buf = b;
       if (!late_barrier) tile_sync(tile);
-      phase_a(buf, 0);             // block 0: scores of block 1 ...
+      phase_a(b, 0);               // block 0: scores of block 1 ...
       if (late_barrier) tile_sync(tile);
-      phase_b(buf_next, 0);        // ... then the K fragments of the next tile's block 0
-      phase_a(buf, 1);             // block 1: scores of the next tile's block 0 ...
-      phase_b(buf_next, 1);        // ... then the K fragments of its block 1
-      buf = buf_next;
+      phase_b(bn, 0);              // ... then the K fragments of the next tile's block 0
+      phase_a(b, 1);               // block 1: scores of the next tile's block 0 ...
+      phase_b(bn, 1);              // ... then the K fragments of its block 1
+      buf = bn;
+      ++tile;
+    };
+    for (;;) {
+      if (tile >= n_plain) break;
+      pipelined_tile(std::integral_constant<int, 0>{});
+      if (tile >= n_plain) break;
+      pipelined_tile(std::integral_constant<int, 1>{});
+      if (tile >= n_plain) break;
+      pipelined_tile(std::integral_constant<int, 2>{});
     }
   }
   // the rest may reach the diagonal: block at a time; the scores of the first such block are in s_next
