@@ -681,33 +681,63 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
 // ---------------------------------------------------------------------------
 // merge of partial results (paper Section 5.1: attention is associative over key slices):
 //   lse = log sum_s exp(lse_s),  out = sum_s exp(lse_s - lse) o_s
-// One thread owns 4 consecutive columns of one row and walks the parts; a part whose lse is -inf
-// has weight 0 and is not read.  D / 4 threads per row, rows packed into 256-thread workgroups.
+// A thread owns 4 consecutive columns of one row and every SL-th part, starting at its split
+// lane; a part whose lse is -inf has weight 0 and is not read.  D / 4 * SL threads per row, rows
+// packed into 256-thread workgroups.  SL = 1 walks all parts in one thread (many rows, few
+// parts); SL = 8 shortens the chain of dependent loads eightfold and adds the lanes' partial
+// sums through LDS (few rows, many parts: small chunks against long prefixes).
 // ---------------------------------------------------------------------------
-template <class T>
+template <typename T, int SL>
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ o_parts,
                                                          const float* __restrict__ lse_parts, int kv_splits,
                                                          int64_t rows, void* __restrict__ out,
                                                          float* __restrict__ lse) {
   constexpr int kThreadsPerRow = T::kD / 4;
-  const int64_t row = (int64_t)blockIdx.x * (256 / kThreadsPerRow) + threadIdx.x / kThreadsPerRow;
-  const int col = (threadIdx.x % kThreadsPerRow) * 4;
-  if (row >= rows) return;
+  constexpr int kRows = 256 / (kThreadsPerRow * SL);     // rows of one workgroup
+  __shared__ float red[kRows][SL];
+  __shared__ f32x4 part[kRows][SL][kThreadsPerRow];
+  const int rl = threadIdx.x / (kThreadsPerRow * SL);
+  const int sl = (threadIdx.x / kThreadsPerRow) % SL;
+  const int cl = threadIdx.x % kThreadsPerRow;
+  const int col = cl * 4;
+  const int64_t row_raw = (int64_t)blockIdx.x * kRows + rl;
+  const bool live = row_raw < rows;
+  const int64_t row = live ? row_raw : rows - 1;         // rows past the end compute the last row again and store nothing
   float m = -INFINITY;
-  for (int s = 0; s < kv_splits; ++s) m = fmaxf(m, lse_parts[(int64_t)s * rows + row]);
+  for (int s = sl; s < kv_splits; s += SL) m = fmaxf(m, lse_parts[(int64_t)s * rows + row]);
+  if constexpr (SL > 1) {
+    if (cl == 0) red[rl][sl] = m;
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < SL; ++t) m = fmaxf(m, red[rl][t]);
+    __syncthreads();
+  }
   float z = 0.f;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   if (m != -INFINITY) {
-    for (int s = 0; s < kv_splits; ++s) {
+    for (int s = sl; s < kv_splits; s += SL) {
       const float w = __expf(lse_parts[(int64_t)s * rows + row] - m);
       if (w == 0.f) continue;
       z += w;
       const f32x4 v = *reinterpret_cast<const f32x4*>(o_parts + ((int64_t)s * rows + row) * T::kD + col);
       acc += w * v;
     }
-    const float inv = 1.0f / z;
-    acc *= inv;
   }
+  if constexpr (SL > 1) {
+    if (cl == 0) red[rl][sl] = z;
+    part[rl][sl][cl] = acc;
+    __syncthreads();
+    if (sl != 0) return;
+    z = 0.f;
+    acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < SL; ++t) {
+      z += red[rl][t];
+      acc += part[rl][t][cl];
+    }
+  }
+  if (!live) return;
+  if (m != -INFINITY) acc *= 1.0f / z;
   T::store4(reinterpret_cast<char*>(out) + row * kRowBytes, col, acc[0], acc[1], acc[2], acc[3]);
   if (lse != nullptr && col == 0) lse[row] = m != -INFINITY ? m + __logf(z) : -INFINITY;
 }
@@ -729,15 +759,24 @@ hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream) {
   return hipGetLastError();
 }
 
+template <typename T, int SL>
+static void enqueue_merge(const float* o_parts, const float* lse_parts, int kv_splits, int64_t rows, void* out,
+                          float* lse, hipStream_t stream) {
+  const int64_t per = 256 / (T::kD / 4 * SL);
+  attn_merge_kernel<T, SL><<<(unsigned)((rows + per - 1) / per), 256, 0, stream>>>(o_parts, lse_parts, kv_splits,
+                                                                                   rows, out, lse);
+}
+
 hipError_t launch_attn_merge(int dtype, const float* o_parts, const float* lse_parts, int kv_splits, int64_t rows,
                              void* out, float* lse, hipStream_t stream) {
   (void)hipGetLastError();
+  const bool wide = kv_splits >= 8;   // enough parts to give each of 8 split lanes one
   if (dtype == MC_DTYPE_BF16) {
-    const int64_t per = 256 / (Bf16::kD / 4);
-    attn_merge_kernel<Bf16><<<(unsigned)((rows + per - 1) / per), 256, 0, stream>>>(o_parts, lse_parts, kv_splits, rows, out, lse);
+    if (wide) enqueue_merge<Bf16, 8>(o_parts, lse_parts, kv_splits, rows, out, lse, stream);
+    else enqueue_merge<Bf16, 1>(o_parts, lse_parts, kv_splits, rows, out, lse, stream);
   } else {
-    const int64_t per = 256 / (F32::kD / 4);
-    attn_merge_kernel<F32><<<(unsigned)((rows + per - 1) / per), 256, 0, stream>>>(o_parts, lse_parts, kv_splits, rows, out, lse);
+    if (wide) enqueue_merge<F32, 8>(o_parts, lse_parts, kv_splits, rows, out, lse, stream);
+    else enqueue_merge<F32, 1>(o_parts, lse_parts, kv_splits, rows, out, lse, stream);
   }
   return hipGetLastError();
 }

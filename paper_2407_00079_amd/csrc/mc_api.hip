@@ -473,10 +473,13 @@ mc_status mc_prefix_hash(const int32_t* tokens, const int64_t* tok_offsets, int3
   std::vector<int64_t> tab(2 * ((size_t)batch + 1));
   int64_t* key_off = tab.data() + batch + 1;
   key_off[0] = 0;
+  int64_t max_blocks = 0;
   for (int32_t r = 0; r < batch; ++r) {
     const int64_t len = tok_offsets[r + 1] - tok_offsets[r];
     if (len < 0 || tok_offsets[r] < 0) return MC_ERR_SHAPE;
-    key_off[r + 1] = key_off[r] + (len + block_tokens - 1) / block_tokens;
+    const int64_t blocks = (len + block_tokens - 1) / block_tokens;
+    key_off[r + 1] = key_off[r] + blocks;
+    max_blocks = blocks > max_blocks ? blocks : max_blocks;
   }
   const int64_t total_blocks = key_off[batch];
   if (total_blocks == 0) return MC_OK;
@@ -484,7 +487,7 @@ mc_status mc_prefix_hash(const int32_t* tokens, const int64_t* tok_offsets, int3
   if ((reinterpret_cast<uintptr_t>(tokens) & 3u) || (reinterpret_cast<uintptr_t>(keys) & 7u) ||
       (reinterpret_cast<uintptr_t>(workspace) & 15u))
     return MC_ERR_ALIGN;
-  if (total_blocks > (int64_t)INT32_MAX * 4 - 8) return MC_ERR_RANGE;
+  if (max_blocks > (1 << 26) - 8) return MC_ERR_RANGE;   // four blocks per workgroup along grid x
   if (workspace == nullptr || workspace_bytes < mc_prefix_hash_workspace_bytes(batch)) return MC_ERR_WORKSPACE;
   std::memcpy(tab.data(), tok_offsets, sizeof(int64_t) * ((size_t)batch + 1));
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
@@ -496,7 +499,7 @@ mc_status mc_prefix_hash(const int32_t* tokens, const int64_t* tok_offsets, int3
   if (hipMemcpyAsync(workspace, host, up, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
   if (!g_staging.release_after(slot, stream)) return MC_ERR_HIP;
   const int64_t* dev_tab = reinterpret_cast<const int64_t*>(workspace);
-  if (mc::launch_prefix_hash(tokens, dev_tab, dev_tab + batch + 1, batch, block_tokens, total_blocks, keys, stream) !=
+  if (mc::launch_prefix_hash(tokens, dev_tab, dev_tab + batch + 1, batch, block_tokens, max_blocks, keys, stream) !=
       hipSuccess)
     return MC_ERR_HIP;
   return MC_OK;

@@ -71,9 +71,9 @@ hipError_t launch_kv_append(const void* k_new, const void* v_new, void* k_pool, 
                             const int32_t* block_tables, int32_t max_pages, const AttnReq* reqs, int32_t batch,
                             int64_t total_new, int32_t Hkv, hipStream_t stream);
 
-// enqueue digest + chain kernels: keys of total_blocks blocks (offset tables on the device)
+// enqueue digest + chain kernels (offset tables on the device; max_blocks = most blocks of any request)
 hipError_t launch_prefix_hash(const int32_t* tokens, const int64_t* tok_off, const int64_t* key_off, int batch,
-                              int block_tokens, int64_t total_blocks, uint64_t* keys, hipStream_t stream);
+                              int block_tokens, int64_t max_blocks, uint64_t* keys, hipStream_t stream);
 
 // enqueue match + best kernels over batch requests and n_inst instances (offset tables on the device)
 hipError_t launch_prefix_match(const uint64_t* keys, const int64_t* key_off, int batch, const uint64_t* cache_keys,
