@@ -288,6 +288,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
   const int n_rows = rq.chunk * G;
   const int last_page = rq.pages - 1;
 
+  // A wave of the second half (these copy no tiles) whose 32 rows all lie past the end of the chunk
+  // has nothing to do: it ends here, and the workgroup's barriers then wait for the surviving
+  // waves only.  Small chunks (a 16-token chunk of an 8-head group fills 4 of 8 waves) then
+  // spend no MFMA work on rows that are never stored.
+  if (wave >= WAVES / 2 && item.row0 + wave * 32 >= n_rows) return;
+
   // ---- this lane's query row: its Q fragments stay in registers for the whole KV loop
   typename T::frag qf[T::kQKSteps];
   int row = item.row0 + wave * 32 + (lane & 31);
