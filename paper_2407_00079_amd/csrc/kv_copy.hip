@@ -58,24 +58,39 @@ __global__ __launch_bounds__(kThreads) void kv_copy_kernel(const u32x4* __restri
   }
 }
 
-// order[r] = the list position whose pool page is the r-th smallest (ties: lower position first).
-// Rank by counting, the id list staged through LDS in chunks: O(n^2 / threads), meant to be run
-// once per request - the list is the same for every layer.
+// order[r] = the list position whose pool page is the r-th smallest (ties: lower position first),
+// i.e. the rank of the 64-bit key (page id, list position).  Rank by counting, the keys staged
+// through LDS in chunks and read back two per LDS instruction, one compare per key:
+// O(n^2 / threads), meant to be run once per request - the list is the same for every layer.
+// Slots past the end of the list hold the largest key and count nothing.
 __global__ __launch_bounds__(256) void kv_page_order_kernel(const int32_t* __restrict__ page_ids, int64_t n,
                                                             int32_t* __restrict__ order) {
-  __shared__ int32_t chunk[1024];
+  typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
+  __shared__ u64x2 chunk[512];
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int32_t mine = i < n ? page_ids[i] : 0;
+  // ids are not negative and positions stay below 2^20: (id << 32) | position orders as the pair does
+  const uint64_t mine = i < n ? ((uint64_t)(uint32_t)page_ids[i] << 32) | (uint64_t)i : 0;
   int64_t rank = 0;
   for (int64_t base = 0; base < n; base += 1024) {
     __syncthreads();
-    for (int t = threadIdx.x; t < 1024; t += 256) chunk[t] = base + t < n ? page_ids[base + t] : INT32_MAX;
-    __syncthreads();
-    const int m = n - base < 1024 ? (int)(n - base) : 1024;
-    for (int t = 0; t < m; ++t) {
-      const int32_t other = chunk[t];
-      rank += (other < mine) || (other == mine && base + t < i);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      u64x2 v;
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int64_t at = base + (threadIdx.x + h * 256) * 2 + e;
+        v[e] = at < n ? ((uint64_t)(uint32_t)page_ids[at] << 32) | (uint64_t)at : ~0ull;
+      }
+      chunk[threadIdx.x + h * 256] = v;
     }
+    __syncthreads();
+    int r = 0;
+#pragma unroll 8
+    for (int t = 0; t < 512; ++t) {
+      const u64x2 o = chunk[t];
+      r += (o[0] < mine) + (o[1] < mine);
+    }
+    rank += r;
   }
   if (i < n) order[rank] = (int32_t)i;
 }
