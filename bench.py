@@ -163,7 +163,18 @@ def main():
 
     def run_steps(count, timed):
         """Layer-wise schedule: load(l+1) is in flight while attention(l) runs; store(l) follows attention(l)."""
-        marks = []
+        marks, copy_marks = [], {"unpack": [], "pack": []}
+
+        def timed_copy(name, fn, l):
+            # events on the copy stream itself, around the one launch
+            if not timed:
+                return fn(l, copy)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(copy)
+            fn(l, copy)
+            b.record(copy)
+            copy_marks[name].append((a, b))
+
         loaded = [torch.cuda.Event() for _ in range(count + 1)]
         attended = [torch.cuda.Event() for _ in range(count)]
         with torch.cuda.stream(copy):
@@ -173,7 +184,7 @@ def main():
             l = i % LAY
             with torch.cuda.stream(copy):
                 if i + 1 < count:
-                    unpack((i + 1) % LAY, copy)
+                    timed_copy("unpack", unpack, (i + 1) % LAY)
                     loaded[i + 1].record(copy)
             with torch.cuda.stream(compute):
                 compute.wait_event(loaded[i])
@@ -188,13 +199,13 @@ def main():
                 attended[i].record(compute)
             with torch.cuda.stream(copy):
                 copy.wait_event(attended[i])
-                pack(l, copy)
-        return marks
+                timed_copy("pack", pack, l)
+        return marks, copy_marks
 
     run_steps(Wm, False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    marks = run_steps(K, True)
+    marks, copy_marks = run_steps(K, True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
@@ -228,6 +239,14 @@ def main():
                      "launch_ms": [round(a.elapsed_time(b), 3) for a, b in marks],
                      "traffic": hbm("attn_config2") if args.attn_config == 2 else None},
     }
+
+    # the copies as they ran inside the step, beside the attention of the neighbouring layer
+    in_step = {}
+    for name, ms in copy_marks.items():
+        us = sorted(a.elapsed_time(b) * 1e3 for a, b in ms)
+        if us:
+            in_step[name] = {"us_median": round(us[len(us) // 2], 2), "us_min": round(us[0], 2), "us_max": round(us[-1], 2)}
+    result["copies_in_step"] = in_step
 
     if not args.no_extra:
         # isolated kernels, same inputs, nothing else running
