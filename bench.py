@@ -417,8 +417,8 @@ def main():
 
     if not args.no_extra:
         # a small chunk against a long prefix (16 new tokens behind 131056 cached ones, 64/8 heads): 8 work
-        # items for 256 CUs unless the keys are split; whole-row kernel vs 32 key slices + merge
-        P2, C2, Hq2, Hkv2, SP = 131056, 16, 64, 8, 32
+        # items for 256 CUs unless the keys are split; whole-row kernel vs the slice count the library suggests + merge
+        P2, C2, Hq2, Hkv2 = 131056, 16, 64, 8
         npg = (P2 + C2) // 16
         g2 = torch.Generator(device=dev)
         g2.manual_seed(20240706)
@@ -427,6 +427,7 @@ def main():
         v2 = torch.randn(npg, Hkv2, 16, 128, device=dev, dtype=torch.bfloat16, generator=g2)
         bt2 = torch.randperm(npg, device=dev, generator=g2).to(torch.int32).reshape(1, npg).contiguous()
         prm = B.attn_params(Hq2, Hkv2, 128, 16, npg, "bf16")
+        SP = B.mc_prefill_attn_suggest_kv_splits(prm, [P2], [C2])
         out2 = torch.empty_like(q2)
         ws_a = torch.empty(B.mc_prefill_attn_workspace_bytes(prm, 1, C2), dtype=torch.uint8, device=dev)
         ws_b = torch.empty(B.mc_prefill_attn_split_workspace_bytes(prm, 1, C2, SP), dtype=torch.uint8, device=dev)

@@ -137,6 +137,20 @@ mc_status mc_prefill_attn_paged_split(const mc_attn_params* p, const void* q, co
                                       size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Number of key slices that fills the GPU for this batch (Section 5.1: long contexts are cut so
+ * that more compute can work on one request): 1 when the whole-row form already gives every
+ * compute unit a work item (use mc_prefill_attn_paged), otherwise the largest count, at most
+ * MC_MAX_KV_SPLITS, that keeps the work items within one per compute unit (256) and leaves
+ * every slice of the longest request at least 8 tiles of 64 keys.  Host arithmetic only: no GPU
+ * call, nothing enqueued.  Returns 0 for arguments mc_prefill_attn_paged would reject as
+ * MC_ERR_NULL / MC_ERR_SHAPE / MC_ERR_UNSUPPORTED.
+ *
+ *   prefix_lens, new_lens  HOST [batch]
+ */
+int32_t mc_prefill_attn_suggest_kv_splits(const mc_attn_params* p, const int32_t* prefix_lens,
+                                          const int32_t* new_lens, int32_t batch);
+
+/*
  * Merge of partial attention results over disjoint key subsets (Section 5.1), whoever produced
  * them (mc_prefill_attn_paged_split, or other GPUs holding other slices of the sequence):
  *

@@ -23,7 +23,7 @@ EXPORTS = ("mc_status_string", "mc_prefill_attn_workspace_bytes", "mc_prefill_at
            "mc_prefill_attn_split_workspace_bytes", "mc_prefill_attn_paged_split", "mc_attn_merge_lse",
            "mc_kv_load_layer", "mc_kv_store_layer", "mc_prefix_hash_workspace_bytes", "mc_prefix_hash",
            "mc_prefix_match_workspace_bytes", "mc_prefix_match", "mc_kv_page_order", "mc_kv_pack_layer_ordered",
-           "mc_kv_unpack_layer_ordered")
+           "mc_kv_unpack_layer_ordered", "mc_prefill_attn_suggest_kv_splits")
 MC_MAX_KV_SPLITS = 256
 
 
@@ -77,6 +77,8 @@ def lib():
                                          ctypes.c_size_t, vp]
         l.mc_prefill_attn_split_workspace_bytes.restype = ctypes.c_size_t
         l.mc_prefill_attn_split_workspace_bytes.argtypes = [ctypes.POINTER(McAttnParams), i32, i64, i32]
+        l.mc_prefill_attn_suggest_kv_splits.restype = ctypes.c_int32
+        l.mc_prefill_attn_suggest_kv_splits.argtypes = [ctypes.POINTER(McAttnParams), vp, vp, i32]
         l.mc_prefill_attn_paged_split.restype = ctypes.c_int
         l.mc_prefill_attn_paged_split.argtypes = [ctypes.POINTER(McAttnParams), vp, vp, vp, vp, i32, vp, vp, i32, i32,
                                                   vp, vp, vp, ctypes.c_size_t, vp]
@@ -149,6 +151,14 @@ def mc_prefill_attn_paged(params: McAttnParams, q, k_pool, v_pool, block_tables,
 def mc_prefill_attn_split_workspace_bytes(params: McAttnParams, batch: int, total_new_tokens: int,
                                           kv_splits: int) -> int:
     return int(lib().mc_prefill_attn_split_workspace_bytes(ctypes.byref(params), batch, total_new_tokens, kv_splits))
+
+
+def mc_prefill_attn_suggest_kv_splits(params: McAttnParams, prefix_lens, new_lens) -> int:
+    """Key slices that fill the GPU for this batch (1: use the whole-row call); 0 for arguments the library rejects."""
+    batch = len(prefix_lens)
+    pl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in prefix_lens])
+    nl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in new_lens])
+    return int(lib().mc_prefill_attn_suggest_kv_splits(ctypes.byref(params), pl, nl, batch))
 
 
 def mc_prefill_attn_paged_split_raw(params, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens,

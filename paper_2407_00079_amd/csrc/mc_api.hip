@@ -295,6 +295,29 @@ mc_status mc_prefill_attn_paged_split(const mc_attn_params* p, const void* q, co
                       nullptr, kv_splits, o_parts, lse_parts, workspace, workspace_bytes, hip_stream);
 }
 
+int32_t mc_prefill_attn_suggest_kv_splits(const mc_attn_params* p, const int32_t* prefix_lens,
+                                          const int32_t* new_lens, int32_t batch) {
+  if (check_params(p) != MC_OK || batch < 0) return 0;
+  if (batch > 0 && (prefix_lens == nullptr || new_lens == nullptr)) return 0;
+  constexpr int64_t kComputeUnits = 256;   // MI355X
+  constexpr int64_t kMinTilesPerSlice = 8;
+  const int64_t tile_rows = mc::attn_tile_rows(p->dtype);
+  const int64_t G = p->num_q_heads / p->num_kv_heads;
+  int64_t items = 0, most_tiles = 0;
+  for (int32_t r = 0; r < batch; ++r) {
+    if (prefix_lens[r] < 0 || new_lens[r] < 0) return 0;
+    if (new_lens[r] == 0) continue;
+    items += (int64_t)p->num_kv_heads * (((int64_t)new_lens[r] * G + tile_rows - 1) / tile_rows);
+    const int64_t tiles = ((int64_t)prefix_lens[r] + new_lens[r] + 63) / 64;
+    most_tiles = tiles > most_tiles ? tiles : most_tiles;
+  }
+  if (items == 0 || items >= kComputeUnits) return 1;
+  int64_t splits = kComputeUnits / items;
+  splits = splits < most_tiles / kMinTilesPerSlice ? splits : most_tiles / kMinTilesPerSlice;
+  splits = splits < MC_MAX_KV_SPLITS ? splits : MC_MAX_KV_SPLITS;
+  return splits < 2 ? 1 : (int32_t)splits;
+}
+
 mc_status mc_attn_merge_lse(const float* o_parts, const float* lse_parts, int32_t kv_splits, int64_t rows,
                             int32_t head_dim, int32_t dtype, void* out, float* lse, void* hip_stream) {
   if (kv_splits < 1 || kv_splits > MC_MAX_KV_SPLITS || rows < 0 || head_dim <= 0) return MC_ERR_SHAPE;

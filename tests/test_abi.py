@@ -118,3 +118,26 @@ def test_copy_argument_errors(lib, fn):
     assert run(num_pages=0) == B.MC_ERR_SHAPE
     assert run(n=2**31) == B.MC_ERR_RANGE
     assert run(n=0, a=None, b=None, c=None, d=None, ids=None) == B.MC_OK
+
+
+def test_suggested_key_slices(lib):
+    """Host arithmetic only: whole-row form when it already gives each of 256 compute units an item, otherwise
+    the count that does, capped by MC_MAX_KV_SPLITS and by 8 tiles of 64 keys per slice of the longest request."""
+    p = good_params()                                            # 64 / 8 heads: 8 stacked rows per token
+    s = B.mc_prefill_attn_suggest_kv_splits
+    assert s(p, [8192], [8192]) == 1                             # 8 heads x 256 row tiles = 2048 items
+    assert s(p, [131056], [16]) == 32                            # 8 items -> 256 / 8
+    assert s(p, [131071], [1]) == 32                             # one token is still one item per KV head
+    assert s(p, [944], [16]) == 1                                # 960 keys = 15 tiles: two slices of 8 do not fit
+    assert s(p, [945], [16]) == 2                                # 961 keys = 16 tiles
+    assert s(p, [32768, 40], [16, 0]) == 32                      # requests without new tokens add no items
+    assert s(p, [32768] * 4, [16] * 4) == 8                      # 32 items -> 8
+    assert s(p, [], []) == 1
+    one = good_params()
+    one.num_q_heads, one.num_kv_heads = 8, 1                     # config-3 heads: one item per 32 tokens
+    assert s(one, [1 << 20], [8]) == B.MC_MAX_KV_SPLITS          # 256 / 1, within the cap
+    assert s(one, [200000], [8192]) == 1                         # 256 row tiles already
+    assert s(p, [-1], [16]) == 0 and s(p, [5], [-2]) == 0
+    bad = good_params()
+    bad.head_dim = 77
+    assert s(bad, [100], [16]) == 0

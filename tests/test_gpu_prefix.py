@@ -24,6 +24,7 @@ def gpu_keys(tokens, off, block_tokens):
     ([131072], 512),                              # one 128k prompt: 256 blocks
     ([37, 5, 64, 63, 129], 16),                   # small blocks: more than one pass of the lanes does not arise
     ([1000] * 40, 100),                           # blocks that are no multiple of the wave width
+    ([3, 0, 9, 1] * 17500 + [5000], 4),           # 70001 requests: more than one request per grid row; one long
 ])
 def test_keys_match_oracle(oracle, lens, block_tokens):
     print(f"prefix hash case lens={lens[:6]} block={block_tokens}", flush=True)

@@ -84,6 +84,21 @@ def test_split_equals_unsplit_kernel_closely(oracle):
     assert np.abs(lse - lse0.reshape(n)).max() <= 2 * TOL[W.BF16]["lse_abs"]
 
 
+def test_suggested_slice_count_runs_and_matches_oracle(oracle):
+    # a 16-token chunk behind 6000 cached tokens: the library suggests a slice count above 1, and that count
+    # (whatever it is) gives the oracle's result
+    case = W.make_attn_case(63, W.BF16, 16, 2, 128, 16, [6000], [16], 400)
+    prm = B.attn_params(16, 2, 128, 16, case.num_pages, "bf16")
+    splits = B.mc_prefill_attn_suggest_kv_splits(prm, case.prefix_lens, case.new_lens)
+    assert 2 <= splits <= B.MC_MAX_KV_SPLITS
+    print(f"suggested kv_splits {splits}", flush=True)
+    _, _, out, lse = run_split(case, splits)
+    rows = all_rows(case)                       # (request, token, head) order = the device's (token, head) order
+    whole, whole_lse, _ = oracle.case_rows(case, rows)
+    check_close(out, whole, W.BF16, "merged")
+    assert np.abs(lse - whole_lse).max() <= TOL[W.BF16]["lse_abs"]
+
+
 def test_merge_of_foreign_partials(oracle):
     # partials that did not come from this library's kernel: -inf parts, NaN payload behind them, all-empty rows
     rng = np.random.default_rng(8)
