@@ -64,6 +64,9 @@ def main():
     ap.add_argument("--layers", type=int, default=8, help="distinct per-layer pools the steps cycle through")
     ap.add_argument("--cpu-rows", type=int, default=65536, help="rows the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-extra", action="store_true", help="skip the isolated / configuration-3 measurements")
+    ap.add_argument("--zero-inputs", action="store_true",
+                    help="DIAGNOSTIC, not a measurement of the workload: Q, K and V all zero (same kernels, same "
+                         "instruction stream, no operand bit activity) to show what the board's power limit costs")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -103,6 +106,9 @@ def main():
             self.k_new = self.k[page, :, pos % c.page_size, :].contiguous()
             self.v_new = self.v[page, :, pos % c.page_size, :].contiguous()
             self.append_ws = torch.empty(B.mc_kv_append_workspace_bytes(c.batch), dtype=torch.uint8, device=dev)
+            if args.zero_inputs:
+                for t in (self.q, self.k, self.v, self.k_new, self.v_new):
+                    t.zero_()
 
         def append(self, stream):
             B.mc_kv_append_paged(self.params, self.k_new, self.v_new, self.k, self.v, self.bt, self.pl, self.nl,
@@ -223,7 +229,8 @@ def main():
         "metric": "prefill attn TFLOP/s (% MFMA peak); KV pack/unpack GB/s (% HBM peak)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic" if not args.zero_inputs else "ALL-ZERO tensors: power diagnostic, not the workload",
         "config": {"workload": f"config {args.attn_config} attention "
                                f"(P={attn.pl if len(attn.pl) < 3 else 'varlen'}, C={attn.nl if len(attn.nl) < 3 else 'varlen'}, "
                                f"{attn.case.num_q_heads}/{attn.case.num_kv_heads} heads, D=128, 16-token pages) "
