@@ -222,6 +222,22 @@ mc_status mc_kv_unpack_layer(const void* k_in, const void* v_in, int64_t num_pag
                              void* k_pool_layer, void* v_pool_layer, void* hip_stream);
 
 /*
+ * Debugging aid for the rule above that ids in device memory are not range-checked by the calls
+ * that use them (an id outside the pool makes those kernels read or write outside it): counts
+ * the ids of a list that lie outside [0, num_pages).
+ *
+ *   page_ids  dev  int32 [n]: a pack / unpack list, or the used part of a block-table row
+ *                  (ceil((P_r + C_r) / page_size) entries; entries past it are never read)
+ *   report    dev  int32 [2]: report[0] = how many ids are outside the range,
+ *                  report[1] = position of the first of them, n if there is none
+ *
+ * Enqueued like everything else: read `report` after the stream has passed the call.  n == 0
+ * enqueues nothing and leaves `report` alone; n > INT32_MAX is MC_ERR_RANGE.
+ */
+mc_status mc_kv_check_page_ids(const int32_t* page_ids, int64_t n, int64_t num_pages, int32_t* report,
+                               void* hip_stream);
+
+/*
  * The same two copies with the order in which the pages are taken chosen by the caller.  A
  * request's page list is the same for all layers, so it pays to compute once
  *

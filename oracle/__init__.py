@@ -259,6 +259,18 @@ def prefix_match(keys, key_offsets, cache_keys, cache_offsets):
     return plen, best_len, best_inst
 
 
+def kv_check_page_ids(page_ids, num_pages: int):
+    """(how many ids lie outside [0, num_pages), position of the first of them or len(page_ids) if none): one pass
+    over the list, by its definition."""
+    count, first = 0, len(page_ids)
+    for i, v in enumerate(page_ids):
+        if int(v) < 0 or int(v) >= num_pages:
+            count += 1
+            if first == len(page_ids):
+                first = i
+    return count, first
+
+
 def kv_page_order(page_ids) -> np.ndarray:
     """order[r] = position in ``page_ids`` of the r-th smallest id, equal ids in list order: the stable
     ascending sort of the positions, by the library's stable argsort."""

@@ -23,7 +23,7 @@ EXPORTS = ("mc_status_string", "mc_prefill_attn_workspace_bytes", "mc_prefill_at
            "mc_prefill_attn_split_workspace_bytes", "mc_prefill_attn_paged_split", "mc_attn_merge_lse",
            "mc_kv_load_layer", "mc_kv_store_layer", "mc_prefix_hash_workspace_bytes", "mc_prefix_hash",
            "mc_prefix_match_workspace_bytes", "mc_prefix_match", "mc_kv_page_order", "mc_kv_pack_layer_ordered",
-           "mc_kv_unpack_layer_ordered", "mc_prefill_attn_suggest_kv_splits")
+           "mc_kv_unpack_layer_ordered", "mc_prefill_attn_suggest_kv_splits", "mc_kv_check_page_ids")
 MC_MAX_KV_SPLITS = 256
 
 
@@ -67,6 +67,8 @@ def lib():
             f.argtypes = [vp, vp, i64, i64, vp, i64, vp, vp, vp]
         l.mc_kv_page_order.restype = ctypes.c_int
         l.mc_kv_page_order.argtypes = [vp, i64, vp, vp]
+        l.mc_kv_check_page_ids.restype = ctypes.c_int
+        l.mc_kv_check_page_ids.argtypes = [vp, i64, i64, vp, vp]
         for f in (l.mc_kv_pack_layer_ordered, l.mc_kv_unpack_layer_ordered):
             f.restype = ctypes.c_int
             f.argtypes = [vp, vp, i64, i64, vp, vp, i64, vp, vp, vp]
@@ -227,6 +229,14 @@ def mc_kv_page_order(page_ids, n: int, order, stream=None) -> None:
     st = int(lib().mc_kv_page_order(_dev_ptr(page_ids), n, _dev_ptr(order), _stream_handle(stream)))
     if st != MC_OK:
         raise McError(st, "mc_kv_page_order")
+
+
+def mc_kv_check_page_ids(page_ids, n: int, num_pages: int, report, stream=None) -> None:
+    """Enqueue the range check of an int32 device id list: report[0] = ids outside [0, num_pages), report[1] =
+    position of the first of them (n if none); ``report`` is an int32 device tensor of 2."""
+    st = int(lib().mc_kv_check_page_ids(_dev_ptr(page_ids), n, num_pages, _dev_ptr(report), _stream_handle(stream)))
+    if st != MC_OK:
+        raise McError(st, "mc_kv_check_page_ids")
 
 
 def mc_kv_pack_layer_ordered(k_pool_layer, v_pool_layer, num_pages: int, page_bytes: int, page_ids, order, n: int,

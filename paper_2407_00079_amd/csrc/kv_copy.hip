@@ -95,6 +95,37 @@ __global__ __launch_bounds__(256) void kv_page_order_kernel(const int32_t* __res
   if (i < n) order[rank] = (int32_t)i;
 }
 
+// Range check of a page id list (debugging aid): a one-thread kernel resets the report, then every
+// wave counts its out-of-range ids and adds them with one atomic; the first position by atomicMin.
+__global__ void kv_check_reset_kernel(int32_t* __restrict__ report, int32_t n) {
+  report[0] = 0;
+  report[1] = n;
+}
+
+__global__ __launch_bounds__(256) void kv_check_page_ids_kernel(const int32_t* __restrict__ page_ids, int64_t n,
+                                                                int64_t num_pages, int32_t* __restrict__ report) {
+  int count = 0;
+  int64_t first = n;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t id = page_ids[i];
+    if (id < 0 || id >= num_pages) {
+      ++count;
+      first = i < first ? i : first;
+    }
+  }
+  if (__builtin_amdgcn_ballot_w64(count != 0) == 0) return;    // the usual case: nothing to report
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    count += __shfl_xor(count, d, 64);
+    const int other = __shfl_xor((int)first, d, 64);
+    first = other < first ? other : first;
+  }
+  if ((threadIdx.x & 63) == 0) {
+    atomicAdd(report, count);
+    atomicMin(report + 1, (int)first);
+  }
+}
+
 // Append (paper Section 3 step 2: the chunk's new KVCache is kept in the request's pages):
 // one thread moves one 16-byte granule of one (token, KV head) row of K and of V.  The request
 // of a token is found by bisection of the per-request table; rows are 256 bytes for both dtypes.
@@ -129,6 +160,15 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const u32x4* __restrict_
 hipError_t launch_kv_page_order(const int32_t* page_ids, int64_t n, int32_t* order, hipStream_t stream) {
   (void)hipGetLastError();
   kv_page_order_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(page_ids, n, order);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_check_page_ids(const int32_t* page_ids, int64_t n, int64_t num_pages, int32_t* report,
+                                    hipStream_t stream) {
+  (void)hipGetLastError();
+  kv_check_reset_kernel<<<1, 1, 0, stream>>>(report, (int32_t)n);
+  const int64_t blocks = (n + 255) / 256;
+  kv_check_page_ids_kernel<<<(unsigned)(blocks < 4096 ? blocks : 4096), 256, 0, stream>>>(page_ids, n, num_pages, report);
   return hipGetLastError();
 }
 

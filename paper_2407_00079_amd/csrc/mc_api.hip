@@ -412,6 +412,19 @@ mc_status mc_kv_page_order(const int32_t* page_ids, int64_t n, int32_t* order, v
   return MC_OK;
 }
 
+mc_status mc_kv_check_page_ids(const int32_t* page_ids, int64_t n, int64_t num_pages, int32_t* report,
+                               void* hip_stream) {
+  if (n < 0 || num_pages < 0) return MC_ERR_SHAPE;
+  if (n == 0) return MC_OK;
+  if (page_ids == nullptr || report == nullptr) return MC_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(page_ids) & 3u) || (reinterpret_cast<uintptr_t>(report) & 3u)) return MC_ERR_ALIGN;
+  if (n > INT32_MAX) return MC_ERR_RANGE;
+  if (mc::launch_kv_check_page_ids(page_ids, n, num_pages, report, reinterpret_cast<hipStream_t>(hip_stream)) !=
+      hipSuccess)
+    return MC_ERR_HIP;
+  return MC_OK;
+}
+
 mc_status mc_kv_pack_layer_ordered(const void* k_pool_layer, const void* v_pool_layer, int64_t num_pages,
                                    int64_t page_bytes, const int32_t* page_ids, const int32_t* order, int64_t n,
                                    void* k_out, void* v_out, void* hip_stream) {

@@ -66,6 +66,10 @@ hipError_t launch_kv_copy(bool pack, const void* k_src, const void* v_src, void*
 // enqueue the computation of order[r] = position of the r-th smallest page id (stable)
 hipError_t launch_kv_page_order(const int32_t* page_ids, int64_t n, int32_t* order, hipStream_t stream);
 
+// enqueue the count of ids outside [0, num_pages) into report[0] and the first such position (n if none) into report[1]
+hipError_t launch_kv_check_page_ids(const int32_t* page_ids, int64_t n, int64_t num_pages, int32_t* report,
+                                    hipStream_t stream);
+
 // enqueue the scatter of total_new tokens' K/V rows (256 bytes per KV head) into their page slots
 hipError_t launch_kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
                             const int32_t* block_tables, int32_t max_pages, const AttnReq* reqs, int32_t batch,

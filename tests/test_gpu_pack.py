@@ -133,3 +133,31 @@ def test_ordered_copies_move_the_same_bytes(oracle, page_bytes, n, N):
         torch.cuda.synchronize()
         np.testing.assert_array_equal(k2.cpu().numpy(), k2_host)
         np.testing.assert_array_equal(v2.cpu().numpy(), v2_host)
+
+
+@pytest.mark.parametrize("n,N,bad_at", [(2048, 4096, ()), (2048, 4096, (5, 1999)), (1, 8, (0,)), (70000, 65536, (69999,)),
+                                        (3_000_000, 1 << 20, (17, 2_000_000, 2_999_999))])
+def test_id_range_check_matches_oracle(oracle, n, N, bad_at):
+    print(f"id check n={n} N={N} bad_at={bad_at}", flush=True)
+    rng = np.random.default_rng(n + len(bad_at))
+    ids = rng.integers(0, N, size=n).astype(np.int32)
+    for j, at in enumerate(bad_at):
+        ids[at] = (N, -1, N + 12345, -(1 << 31))[j % 4]
+    report = torch.full((2,), 77, dtype=torch.int32, device="cuda:0")
+    B.mc_kv_check_page_ids(_dev(ids), n, N, report)
+    torch.cuda.synchronize()
+    want = (len(bad_at), min(bad_at) if bad_at else n)          # what was planted ...
+    assert tuple(report.cpu().tolist()) == want
+    if n <= 100000:
+        assert oracle.kv_check_page_ids(ids, N) == want          # ... and what the oracle's pass over the list finds
+
+
+def test_id_range_check_noop_and_rejections():
+    report = torch.full((2,), 77, dtype=torch.int32, device="cuda:0")
+    B.mc_kv_check_page_ids(None, 0, 8, report)                   # n == 0: nothing enqueued, report untouched
+    torch.cuda.synchronize()
+    assert report.cpu().tolist() == [77, 77]
+    with pytest.raises(B.McError):
+        B.mc_kv_check_page_ids(None, 4, 8, report)
+    with pytest.raises(B.McError):
+        B.mc_kv_check_page_ids(report, -1, 8, report)

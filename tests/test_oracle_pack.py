@@ -102,3 +102,11 @@ def test_page_order_is_the_stable_ascending_permutation(oracle):
         assert sorted(order.tolist()) == list(range(n))                       # a permutation of the positions
         for a, b in zip(order[:-1], order[1:]):                                # by definition, pair by pair
             assert ids[a] < ids[b] or (ids[a] == ids[b] and a < b)
+
+
+def test_id_range_check_by_hand(oracle):
+    # ids 7 and -1 and 5 are outside a pool of 5 pages; the first of them sits at position 2
+    assert oracle.kv_check_page_ids([0, 4, 7, 3, -1, 5, 2], 5) == (3, 2)
+    assert oracle.kv_check_page_ids([0, 4, 3], 5) == (0, 3)
+    assert oracle.kv_check_page_ids([], 5) == (0, 0)
+    assert oracle.kv_check_page_ids([5], 5) == (1, 0)
