@@ -138,12 +138,14 @@ mc_status mc_prefill_attn_paged_split(const mc_attn_params* p, const void* q, co
 
 /*
  * Number of key slices that fills the GPU for this batch (Section 5.1: long contexts are cut so
- * that more compute can work on one request): 1 when the whole-row form already gives every
- * compute unit a work item (use mc_prefill_attn_paged), otherwise the largest count, at most
- * MC_MAX_KV_SPLITS, that keeps the work items within one per compute unit (256) and leaves
- * every slice of the longest request at least 8 tiles of 64 keys.  Host arithmetic only: no GPU
- * call, nothing enqueued.  Returns 0 for arguments mc_prefill_attn_paged would reject as
- * MC_ERR_NULL / MC_ERR_SHAPE / MC_ERR_UNSUPPORTED.
+ * that more compute can work on one request).  With n work items in the whole-row form (one per
+ * request, KV head and tile of stacked query rows) and 256 compute units, s slices take
+ * ceil(n s / 256) / s rounds of the whole-row item length, and every slice beyond the first adds
+ * about 1 % for the partial results: the count with the least cost wins, among those that leave
+ * every slice of the longest request at least 8 tiles of 64 keys and do not exceed
+ * MC_MAX_KV_SPLITS.  1 means mc_prefill_attn_paged is the better call (always so from 1024 work
+ * items on).  Host arithmetic only: no GPU call, nothing enqueued.  Returns 0 for arguments
+ * mc_prefill_attn_paged would reject as MC_ERR_NULL / MC_ERR_SHAPE / MC_ERR_UNSUPPORTED.
  *
  *   prefix_lens, new_lens  HOST [batch]
  */

@@ -121,8 +121,8 @@ def test_copy_argument_errors(lib, fn):
 
 
 def test_suggested_key_slices(lib):
-    """Host arithmetic only: whole-row form when it already gives each of 256 compute units an item, otherwise
-    the count that does, capped by MC_MAX_KV_SPLITS and by 8 tiles of 64 keys per slice of the longest request."""
+    """Host arithmetic only: the slice count with the fewest rounds of 256 work items (1 % per extra slice),
+    capped by MC_MAX_KV_SPLITS and by 8 tiles of 64 keys per slice of the longest request."""
     p = good_params()                                            # 64 / 8 heads: 8 stacked rows per token
     s = B.mc_prefill_attn_suggest_kv_splits
     assert s(p, [8192], [8192]) == 1                             # 8 heads x 256 row tiles = 2048 items
@@ -136,7 +136,11 @@ def test_suggested_key_slices(lib):
     one = good_params()
     one.num_q_heads, one.num_kv_heads = 8, 1                     # config-3 heads: one item per 32 tokens
     assert s(one, [1 << 20], [8]) == B.MC_MAX_KV_SPLITS          # 256 / 1, within the cap
-    assert s(one, [200000], [8192]) == 1                         # 256 row tiles already
+    assert s(one, [200000], [8192]) == 1                         # 256 items: one full round
+    assert s(one, [120832], [10240]) == 4                        # 320 items: 2 rounds whole, 5 rounds of quarters
+    assert s(one, [110592], [20480]) == 2                        # 640 items: 3 rounds whole, 5 rounds of halves
+    assert s(one, [114688], [16384]) == 1                        # 512 items: two full rounds
+    assert s(one, [1 << 20], [40000]) == 1                       # 1250 items: the launch order balances the tail
     assert s(p, [-1], [16]) == 0 and s(p, [5], [-2]) == 0
     bad = good_params()
     bad.head_dim = 77
