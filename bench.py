@@ -423,47 +423,53 @@ def main():
             torch.cuda.empty_cache()
 
     if not args.no_extra:
+        def whole_vs_split(P2, C2, Hq2, Hkv2, iters):
+            """Whole-row kernel against the slice count the library suggests + merge, one request."""
+            npg = (P2 + C2) // 16
+            g2 = torch.Generator(device=dev)
+            g2.manual_seed(20240706)
+            q2 = torch.randn(C2, Hq2, 128, device=dev, dtype=torch.bfloat16, generator=g2)
+            k2 = torch.randn(npg, Hkv2, 16, 128, device=dev, dtype=torch.bfloat16, generator=g2)
+            v2 = torch.randn(npg, Hkv2, 16, 128, device=dev, dtype=torch.bfloat16, generator=g2)
+            bt2 = torch.randperm(npg, device=dev, generator=g2).to(torch.int32).reshape(1, npg).contiguous()
+            prm = B.attn_params(Hq2, Hkv2, 128, 16, npg, "bf16")
+            SP = B.mc_prefill_attn_suggest_kv_splits(prm, [P2], [C2])
+            out2 = torch.empty_like(q2)
+            ws_a = torch.empty(B.mc_prefill_attn_workspace_bytes(prm, 1, C2), dtype=torch.uint8, device=dev)
+            ws_b = torch.empty(B.mc_prefill_attn_split_workspace_bytes(prm, 1, C2, SP), dtype=torch.uint8, device=dev)
+            o_parts = torch.empty(SP, C2, Hq2, 128, device=dev, dtype=torch.float32)
+            l_parts = torch.empty(SP, C2, Hq2, device=dev, dtype=torch.float32)
+            s = torch.cuda.current_stream()
+
+            def whole():
+                B.mc_prefill_attn_paged(prm, q2, k2, v2, bt2, [P2], [C2], out2, None, ws_a, s)
+
+            def split():
+                B.mc_prefill_attn_paged_split(prm, q2, k2, v2, bt2, [P2], [C2], SP, o_parts, l_parts, ws_b, s)
+                B.mc_attn_merge_lse(o_parts, l_parts, SP, C2 * Hq2, 128, B.MC_DTYPE_BF16, out2, None, s)
+
+            fl2 = 4 * 128 * Hq2 * (C2 * P2 + C2 * (C2 + 1) // 2)
+            rec = {"workload": f"{Hq2}/{Hkv2} heads, P={P2}, C={C2}", "flops": fl2}
+            for name, fn in (("whole_row", whole), (f"split{SP}_plus_merge", split)):
+                for _ in range(3):
+                    fn()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(s)
+                for _ in range(iters):
+                    fn()
+                b.record(s)
+                torch.cuda.synchronize()
+                us = a.elapsed_time(b) * 1e3 / iters
+                rec[name] = {"us": round(us, 1), "tflops": round(fl2 / (us * 1e-6) / 1e12, 1)}
+            return rec
+
         # a small chunk against a long prefix (16 new tokens behind 131056 cached ones, 64/8 heads): 8 work
-        # items for 256 CUs unless the keys are split; whole-row kernel vs the slice count the library suggests + merge
-        P2, C2, Hq2, Hkv2 = 131056, 16, 64, 8
-        npg = (P2 + C2) // 16
-        g2 = torch.Generator(device=dev)
-        g2.manual_seed(20240706)
-        q2 = torch.randn(C2, Hq2, 128, device=dev, dtype=torch.bfloat16, generator=g2)
-        k2 = torch.randn(npg, Hkv2, 16, 128, device=dev, dtype=torch.bfloat16, generator=g2)
-        v2 = torch.randn(npg, Hkv2, 16, 128, device=dev, dtype=torch.bfloat16, generator=g2)
-        bt2 = torch.randperm(npg, device=dev, generator=g2).to(torch.int32).reshape(1, npg).contiguous()
-        prm = B.attn_params(Hq2, Hkv2, 128, 16, npg, "bf16")
-        SP = B.mc_prefill_attn_suggest_kv_splits(prm, [P2], [C2])
-        out2 = torch.empty_like(q2)
-        ws_a = torch.empty(B.mc_prefill_attn_workspace_bytes(prm, 1, C2), dtype=torch.uint8, device=dev)
-        ws_b = torch.empty(B.mc_prefill_attn_split_workspace_bytes(prm, 1, C2, SP), dtype=torch.uint8, device=dev)
-        o_parts = torch.empty(SP, C2, Hq2, 128, device=dev, dtype=torch.float32)
-        l_parts = torch.empty(SP, C2, Hq2, device=dev, dtype=torch.float32)
-        s = torch.cuda.current_stream()
-
-        def whole():
-            B.mc_prefill_attn_paged(prm, q2, k2, v2, bt2, [P2], [C2], out2, None, ws_a, s)
-
-        def split():
-            B.mc_prefill_attn_paged_split(prm, q2, k2, v2, bt2, [P2], [C2], SP, o_parts, l_parts, ws_b, s)
-            B.mc_attn_merge_lse(o_parts, l_parts, SP, C2 * Hq2, 128, B.MC_DTYPE_BF16, out2, None, s)
-
-        fl2 = 4 * 128 * Hq2 * (C2 * P2 + C2 * (C2 + 1) // 2)
-        small = {"workload": f"64/8 heads, P={P2}, C={C2}", "flops": fl2}
-        for name, fn in (("whole_row", whole), (f"split{SP}_plus_merge", split)):
-            for _ in range(3):
-                fn()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(s)
-            for _ in range(20):
-                fn()
-            b.record(s)
-            torch.cuda.synchronize()
-            us = a.elapsed_time(b) * 1e3 / 20
-            small[name] = {"us": round(us, 1), "tflops": round(fl2 / (us * 1e-6) / 1e12, 1)}
-        result["attn_small_chunk"] = small
-        del q2, k2, v2, o_parts, l_parts
+        # items for 256 CUs unless the keys are split
+        result["attn_small_chunk"] = whole_vs_split(131056, 16, 64, 8, 20)
+        # just above one work item per compute unit (10240 new tokens, 8/1 heads: 320 items): the whole-row form
+        # runs a second, mostly empty round
+        result["attn_uneven_rounds"] = whole_vs_split(120832, 10240, 8, 1, 6)
+        torch.cuda.empty_cache()
         torch.cuda.synchronize()
         ceil = mfma_ceiling()
         if ceil is not None:
