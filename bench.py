@@ -118,7 +118,7 @@ def main():
             B.mc_prefill_attn_paged(self.params, self.q, self.k, self.v, self.bt, self.pl, self.nl, self.out,
                                     self.lse, self.ws, stream)
 
-        def time_isolated(self, iters=10, warm=3):
+        def time_isolated(self, iters=20, warm=5):
             s = torch.cuda.current_stream()
             for _ in range(warm):
                 self.launch(s)
@@ -415,7 +415,7 @@ def main():
             if idx == args.attn_config:
                 continue
             other = Attn(idx)
-            med, mn = other.time_isolated(iters=6 if idx == 4 else 10)
+            med, mn = other.time_isolated()
             result[f"attn_config{idx}"] = {"workload": labels[idx], "flops": other.flops, "ms_median": round(med, 4),
                                           "ms_min": round(mn, 4), "tflops": round(other.flops / (med * 1e-3) / 1e12, 2),
                                           "pct_mfma_peak": round(100 * other.flops / (med * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2)}
