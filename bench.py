@@ -284,6 +284,31 @@ def main():
                                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                                           "us_per_layer": round(us, 2), "bytes_per_launch": copy_bytes,
                                           "traffic": hbm(name.split("_")[0])}
+        # what a copy of the same bytes reaches on this board with nothing scattered: the same kernel with the pages
+        # in pool order (ids 0 .. n-1), and the runtime's device-to-device copy
+        seq_ids = torch.arange(n, dtype=torch.int32, device=dev)
+
+        def pack_contiguous(l, stream):
+            B.mc_kv_pack_layer(k_pool[l], v_pool[l], N2, pb, seq_ids, n, k_store[l], v_store[l], stream)
+
+        def runtime_copy(l, stream):
+            k_store[l].copy_(k_pool[l, :n])
+            v_store[l].copy_(v_pool[l, :n])
+
+        ceiling = {}
+        for name, fn in (("same_kernel_contiguous", pack_contiguous), ("runtime_d2d_copy", runtime_copy)):
+            for l in range(LAY):
+                fn(l, s)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(s)
+            for i in range(80):
+                fn(i % LAY, s)
+            b.record(s)
+            torch.cuda.synchronize()
+            us = a.elapsed_time(b) * 1e3 / 80
+            ceiling[name] = {"GBs": round(copy_bytes / (us * 1e-6) / 1e9, 1), "us_per_layer": round(us, 2),
+                             "frac_hbm_peak": round(copy_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+        result["copy_ceiling"] = {"what": "the same 2 x 64 MiB read and written with no scatter at all", **ceiling}
         # append of the step's chunk alone, launched back to back
         c = attn.case
         for _ in range(5):
