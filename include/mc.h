@@ -153,6 +153,32 @@ int32_t mc_prefill_attn_suggest_kv_splits(const mc_attn_params* p, const int32_t
                                           const int32_t* new_lens, int32_t batch);
 
 /*
+ * The work list the two attention calls above launch for these lengths, in launch order, written
+ * to HOST memory - for inspection and for tests of the host logic; no GPU call, nothing enqueued.
+ * One work item = one workgroup = one tile of 256 stacked query rows (row = token * G + head in
+ * group) of one (request, KV head), and for the split form one key slice of it:
+ *
+ *   items[i] = { request, kv_head, first stacked row of the tile, key slice (0 if whole-row) }
+ *
+ * Order: items are keyed by the keys their last row sees (split form: by the keys of the slice),
+ * kept in 8 lists by (request * Hkv + kv_head + slice) mod 8, longest first within a list, and
+ * dealt out round-robin - consecutive workgroups land on different XCDs, so each XCD's L2 keeps
+ * the K/V stream of one (request, KV head), and the longest items start first.
+ *
+ *   kv_splits  0 = mc_prefill_attn_paged, 1 .. MC_MAX_KV_SPLITS = mc_prefill_attn_paged_split
+ *   items      HOST int32 [capacity][4], or NULL (capacity 0) to count only
+ *   n_items    HOST out: the number of work items (set whenever the status is MC_OK or
+ *              MC_ERR_WORKSPACE)
+ *
+ * Status: what the attention call would answer to the same params and lengths (MC_ERR_NULL,
+ * MC_ERR_SHAPE, MC_ERR_UNSUPPORTED, MC_ERR_RANGE); MC_ERR_WORKSPACE when capacity < n_items
+ * (nothing written to items then).
+ */
+mc_status mc_prefill_attn_plan(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens,
+                               int32_t batch, int32_t kv_splits, int32_t* items, int64_t capacity,
+                               int64_t* n_items);
+
+/*
  * Merge of partial attention results over disjoint key subsets (Section 5.1), whoever produced
  * them (mc_prefill_attn_paged_split, or other GPUs holding other slices of the sequence):
  *

@@ -23,7 +23,8 @@ EXPORTS = ("mc_status_string", "mc_prefill_attn_workspace_bytes", "mc_prefill_at
            "mc_prefill_attn_split_workspace_bytes", "mc_prefill_attn_paged_split", "mc_attn_merge_lse",
            "mc_kv_load_layer", "mc_kv_store_layer", "mc_prefix_hash_workspace_bytes", "mc_prefix_hash",
            "mc_prefix_match_workspace_bytes", "mc_prefix_match", "mc_kv_page_order", "mc_kv_pack_layer_ordered",
-           "mc_kv_unpack_layer_ordered", "mc_prefill_attn_suggest_kv_splits", "mc_kv_check_page_ids")
+           "mc_kv_unpack_layer_ordered", "mc_prefill_attn_suggest_kv_splits", "mc_kv_check_page_ids",
+           "mc_prefill_attn_plan")
 MC_MAX_KV_SPLITS = 256
 
 
@@ -79,6 +80,8 @@ def lib():
                                          ctypes.c_size_t, vp]
         l.mc_prefill_attn_split_workspace_bytes.restype = ctypes.c_size_t
         l.mc_prefill_attn_split_workspace_bytes.argtypes = [ctypes.POINTER(McAttnParams), i32, i64, i32]
+        l.mc_prefill_attn_plan.restype = ctypes.c_int
+        l.mc_prefill_attn_plan.argtypes = [ctypes.POINTER(McAttnParams), vp, vp, i32, i32, vp, i64, vp]
         l.mc_prefill_attn_suggest_kv_splits.restype = ctypes.c_int32
         l.mc_prefill_attn_suggest_kv_splits.argtypes = [ctypes.POINTER(McAttnParams), vp, vp, i32]
         l.mc_prefill_attn_paged_split.restype = ctypes.c_int
@@ -153,6 +156,23 @@ def mc_prefill_attn_paged(params: McAttnParams, q, k_pool, v_pool, block_tables,
 def mc_prefill_attn_split_workspace_bytes(params: McAttnParams, batch: int, total_new_tokens: int,
                                           kv_splits: int) -> int:
     return int(lib().mc_prefill_attn_split_workspace_bytes(ctypes.byref(params), batch, total_new_tokens, kv_splits))
+
+
+def mc_prefill_attn_plan(params: McAttnParams, prefix_lens, new_lens, kv_splits: int = 0):
+    """The work list of an attention launch, in launch order: a list of (request, kv_head, row0, slice) tuples.
+    Host arithmetic only (no GPU)."""
+    batch = len(prefix_lens)
+    pl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in prefix_lens])
+    nl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in new_lens])
+    n = ctypes.c_int64(-1)
+    st = int(lib().mc_prefill_attn_plan(ctypes.byref(params), pl, nl, batch, kv_splits, None, 0, ctypes.byref(n)))
+    if st != MC_OK:
+        raise McError(st, "mc_prefill_attn_plan")
+    buf = (ctypes.c_int32 * (4 * max(n.value, 1)))()
+    st = int(lib().mc_prefill_attn_plan(ctypes.byref(params), pl, nl, batch, kv_splits, buf, n.value, ctypes.byref(n)))
+    if st != MC_OK:
+        raise McError(st, "mc_prefill_attn_plan")
+    return [tuple(buf[4 * i:4 * i + 4]) for i in range(n.value)]
 
 
 def mc_prefill_attn_suggest_kv_splits(params: McAttnParams, prefix_lens, new_lens) -> int:

@@ -134,6 +134,66 @@ size_t mc_prefill_attn_workspace_bytes(const mc_attn_params* p, int32_t batch, i
 
 namespace {
 
+// Work list of an attention launch: one item per (request, KV head, tile of stacked rows) and, for
+// split launches (kv_splits >= 1), per key slice - most keys first, dealt round-robin so that
+// consecutive workgroup ids (which land on different XCDs) take different (request, KV head)
+// streams and each XCD's L2 keeps one stream hot.  Lengths have been validated by the caller.
+void build_work_list(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch,
+                     int32_t kv_splits, std::vector<mc::AttnReq>& reqs, std::vector<mc::AttnItem>& items) {
+  const bool split = kv_splits > 0;
+  const int G = p->num_q_heads / p->num_kv_heads;
+  const int rows = mc::attn_tile_rows(p->dtype);
+  reqs.assign((size_t)batch, mc::AttnReq{});
+  struct Keyed {
+    int64_t cost;
+    mc::AttnItem it;
+  };
+  constexpr int kXcd = 8;
+  std::vector<Keyed> lanes[kXcd];
+  int64_t q_off = 0;
+  for (int32_t r = 0; r < batch; ++r) {
+    const int32_t P = prefix_lens[r], C = new_lens[r];
+    reqs[(size_t)r] = {(int32_t)q_off, P, C, (int32_t)(((int64_t)P + C + p->page_size - 1) / p->page_size)};
+    q_off += C;
+    const int64_t n_rows = (int64_t)C * G;
+    for (int32_t g = 0; g < p->num_kv_heads; ++g)
+      for (int64_t row0 = 0; row0 < n_rows; row0 += rows) {
+        const int64_t tok_last = std::min<int64_t>(C - 1, (row0 + rows - 1) / G);
+        const int64_t keys = P + tok_last + 1;                 // keys the tile's last row sees
+        if (!split) {
+          lanes[(r * p->num_kv_heads + g) % kXcd].push_back({keys, {r, g, (int32_t)row0, 0}});
+          continue;
+        }
+        // slices of whole 64-key tiles, ceil(tiles of the request / kv_splits) each; every slice gets
+        // an item, also one past what the tile can see (it writes zeros and -inf)
+        const int64_t per = ((((int64_t)P + C + 63) / 64) + kv_splits - 1) / kv_splits * 64;
+        for (int32_t sl = 0; sl < kv_splits; ++sl) {
+          const int64_t cost = std::max<int64_t>(0, std::min<int64_t>(keys, (sl + 1) * per) - sl * per);
+          lanes[(r * p->num_kv_heads + g + sl) % kXcd].push_back({cost, {r, g, (int32_t)row0, sl}});
+        }
+      }
+  }
+  size_t n_items = 0;
+  for (auto& l : lanes) {
+    std::stable_sort(l.begin(), l.end(), [](const Keyed& a, const Keyed& b) { return a.cost > b.cost; });
+    n_items += l.size();
+  }
+  items.clear();
+  items.reserve(n_items);
+  size_t cur[kXcd] = {0};
+  int x = 0;
+  while (items.size() < n_items) {
+    // next non-empty lane, starting from the one whose turn it is
+    int tries = 0;
+    while (cur[x] >= lanes[x].size() && tries < kXcd) {
+      x = (x + 1) % kXcd;
+      ++tries;
+    }
+    items.push_back(lanes[x][cur[x]++].it);
+    x = (x + 1) % kXcd;
+  }
+}
+
 // kv_splits == 0: the whole-row kernel writes out / lse.  kv_splits >= 1: the split kernel writes
 // partials (out / lse unused).
 mc_status attn_enqueue(const mc_attn_params* p, const void* q, const void* k_pool, const void* v_pool,
@@ -171,61 +231,10 @@ mc_status attn_enqueue(const mc_attn_params* p, const void* q, const void* k_poo
       workspace_bytes < sizeof(mc::AttnItem) * n_max + sizeof(mc::AttnReq) * (size_t)batch + 64)
     return MC_ERR_WORKSPACE;
 
-  // ---- work list: one item per (request, KV head, tile of stacked rows), most keys first,
-  //      dealt round-robin so that consecutive workgroup ids (which land on different XCDs)
-  //      take different (request, KV head) streams and each XCD's L2 keeps one stream hot
-  const int rows = mc::attn_tile_rows(p->dtype);
-  std::vector<mc::AttnReq> reqs((size_t)batch);
-  struct Keyed {
-    int64_t cost;
-    mc::AttnItem it;
-  };
-  constexpr int kXcd = 8;
-  std::vector<Keyed> lanes[kXcd];
-  int64_t q_off = 0;
-  for (int32_t r = 0; r < batch; ++r) {
-    const int32_t P = prefix_lens[r], C = new_lens[r];
-    reqs[(size_t)r] = {(int32_t)q_off, P, C, (int32_t)(((int64_t)P + C + p->page_size - 1) / p->page_size)};
-    q_off += C;
-    const int64_t n_rows = (int64_t)C * G;
-    for (int32_t g = 0; g < p->num_kv_heads; ++g)
-      for (int64_t row0 = 0; row0 < n_rows; row0 += rows) {
-        const int64_t tok_last = std::min<int64_t>(C - 1, (row0 + rows - 1) / G);
-        const int64_t keys = P + tok_last + 1;                 // keys the tile's last row sees
-        if (!split) {
-          lanes[(r * p->num_kv_heads + g) % kXcd].push_back({keys, {r, g, (int32_t)row0, 0}});
-          continue;
-        }
-        // slices of whole 64-key tiles, ceil(tiles of the request / kv_splits) each; every slice gets
-        // an item, also one past what the tile can see (it writes zeros and -inf)
-        const int64_t per = ((((int64_t)P + C + 63) / 64) + kv_splits - 1) / kv_splits * 64;
-        for (int32_t sl = 0; sl < kv_splits; ++sl) {
-          const int64_t cost = std::max<int64_t>(0, std::min<int64_t>(keys, (sl + 1) * per) - sl * per);
-          lanes[(r * p->num_kv_heads + g + sl) % kXcd].push_back({cost, {r, g, (int32_t)row0, sl}});
-        }
-      }
-  }
+  std::vector<mc::AttnReq> reqs;
   std::vector<mc::AttnItem> items;
-  size_t n_items = 0;
-  for (auto& l : lanes) {
-    std::stable_sort(l.begin(), l.end(), [](const Keyed& a, const Keyed& b) { return a.cost > b.cost; });
-    n_items += l.size();
-  }
-  items.reserve(n_items);
-  {
-    size_t cur[kXcd] = {0};
-    int x = 0;
-    while (items.size() < n_items) {
-      // next non-empty lane, starting from the one whose turn it is
-      int tries = 0;
-      while (cur[x] >= lanes[x].size() && tries < kXcd) {
-        x = (x + 1) % kXcd;
-        ++tries;
-      }
-      items.push_back(lanes[x][cur[x]++].it);
-      x = (x + 1) % kXcd;
-    }
-  }
+  build_work_list(p, prefix_lens, new_lens, batch, split ? kv_splits : 0, reqs, items);
+  const size_t n_items = items.size();
 
   // ---- upload work list + request table into the caller's workspace (one pinned, async copy)
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
@@ -293,6 +302,32 @@ mc_status mc_prefill_attn_paged_split(const mc_attn_params* p, const void* q, co
   if (kv_splits < 1 || kv_splits > MC_MAX_KV_SPLITS) return MC_ERR_SHAPE;
   return attn_enqueue(p, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens, batch, nullptr,
                       nullptr, kv_splits, o_parts, lse_parts, workspace, workspace_bytes, hip_stream);
+}
+
+mc_status mc_prefill_attn_plan(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens,
+                               int32_t batch, int32_t kv_splits, int32_t* items, int64_t capacity,
+                               int64_t* n_items) {
+  mc_status st = check_params(p);
+  if (st != MC_OK) return st;
+  if (batch < 0 || kv_splits < 0 || kv_splits > MC_MAX_KV_SPLITS || capacity < 0) return MC_ERR_SHAPE;
+  if (n_items == nullptr || (batch > 0 && (prefix_lens == nullptr || new_lens == nullptr))) return MC_ERR_NULL;
+  if (capacity > 0 && items == nullptr) return MC_ERR_NULL;
+  int64_t total_new = 0;
+  for (int32_t r = 0; r < batch; ++r) {
+    if (prefix_lens[r] < 0 || new_lens[r] < 0) return MC_ERR_SHAPE;
+    if ((int64_t)prefix_lens[r] + new_lens[r] > INT32_MAX - 1024) return MC_ERR_RANGE;
+    total_new += new_lens[r];
+  }
+  if (total_new * p->num_q_heads > INT32_MAX) return MC_ERR_RANGE;
+  if (max_items(p, batch, total_new, kv_splits > 0 ? kv_splits : 1) > (size_t)INT32_MAX) return MC_ERR_RANGE;
+  std::vector<mc::AttnReq> reqs;
+  std::vector<mc::AttnItem> list;
+  build_work_list(p, prefix_lens, new_lens, batch, kv_splits, reqs, list);
+  *n_items = (int64_t)list.size();
+  if ((int64_t)list.size() > capacity) return capacity == 0 && items == nullptr ? MC_OK : MC_ERR_WORKSPACE;
+  static_assert(sizeof(mc::AttnItem) == 4 * sizeof(int32_t), "an item is four int32");
+  if (!list.empty()) std::memcpy(items, list.data(), sizeof(mc::AttnItem) * list.size());
+  return MC_OK;
 }
 
 int32_t mc_prefill_attn_suggest_kv_splits(const mc_attn_params* p, const int32_t* prefix_lens,
