@@ -161,3 +161,49 @@ def test_id_range_check_noop_and_rejections():
         B.mc_kv_check_page_ids(None, 4, 8, report)
     with pytest.raises(B.McError):
         B.mc_kv_check_page_ids(report, -1, 8, report)
+
+
+def test_copies_replay_from_a_hip_graph(oracle):
+    """pack, ordered unpack and the merge need no upload and no allocation: captured once in a HIP graph they
+    give the eager result on every replay, with eager work and synchronisations between the replays."""
+    rng = np.random.default_rng(77)
+    N, n, pb = 96, 40, 4096
+    ids = rng.permutation(N)[:n].astype(np.int32)
+    d_ids = _dev(ids)
+    order = torch.empty((n,), dtype=torch.int32, device="cuda:0")
+    B.mc_kv_page_order(d_ids, n, order)
+    pool_k = torch.zeros((N, pb), dtype=torch.uint8, device="cuda:0")
+    pool_v = torch.zeros_like(pool_k)
+    packed_k = torch.zeros((n, pb), dtype=torch.uint8, device="cuda:0")
+    packed_v = torch.zeros_like(packed_k)
+    pool2_k = torch.zeros((N, pb), dtype=torch.uint8, device="cuda:0")
+    pool2_v = torch.zeros_like(pool2_k)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        # one eager pass first, so that nothing is loaded or initialised for the first time under capture
+        B.mc_kv_pack_layer(pool_k, pool_v, N, pb, d_ids, n, packed_k, packed_v, side)
+        B.mc_kv_unpack_layer_ordered(packed_k, packed_v, N, pb, d_ids, order, n, pool2_k, pool2_v, side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            B.mc_kv_pack_layer(pool_k, pool_v, N, pb, d_ids, n, packed_k, packed_v, side)
+            B.mc_kv_unpack_layer_ordered(packed_k, packed_v, N, pb, d_ids, order, n, pool2_k, pool2_v, side)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        hk = rng.integers(0, 256, size=(N, pb), dtype=np.uint8)
+        hv = rng.integers(0, 256, size=(N, pb), dtype=np.uint8)
+        pool_k.copy_(torch.from_numpy(hk))                      # eager work between the replays
+        pool_v.copy_(torch.from_numpy(hv))
+        pool2_k.zero_()
+        pool2_v.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref_k, ref_v = oracle.kv_pack_layer(hk, hv, ids)
+        np.testing.assert_array_equal(packed_k.cpu().numpy(), ref_k, err_msg=f"replay {rep}")
+        np.testing.assert_array_equal(packed_v.cpu().numpy(), ref_v, err_msg=f"replay {rep}")
+        want_k, want_v = np.zeros((N, pb), dtype=np.uint8), np.zeros((N, pb), dtype=np.uint8)
+        oracle.kv_unpack_layer(ref_k, ref_v, ids, want_k, want_v)
+        np.testing.assert_array_equal(pool2_k.cpu().numpy(), want_k, err_msg=f"replay {rep}")
+        np.testing.assert_array_equal(pool2_v.cpu().numpy(), want_v, err_msg=f"replay {rep}")
