@@ -488,6 +488,36 @@ def main():
                 rec[name] = {"us": round(us, 1), "tflops": round(fl2 / (us * 1e-6) / 1e12, 1)}
             return rec
 
+        # the fp32 instantiation (configuration 1's arithmetic) at configuration 2's lengths, against the fp32 MFMA peak
+        def fp32_attention():
+            P2, C2, Hq2, Hkv2 = 8192, 8192, 64, 8
+            npg = (P2 + C2) // 16
+            g2 = torch.Generator(device=dev)
+            g2.manual_seed(20240701)
+            q2 = torch.randn(C2, Hq2, 64, device=dev, dtype=torch.float32, generator=g2)
+            k2 = torch.randn(npg, Hkv2, 16, 64, device=dev, dtype=torch.float32, generator=g2)
+            v2 = torch.randn(npg, Hkv2, 16, 64, device=dev, dtype=torch.float32, generator=g2)
+            bt2 = torch.randperm(npg, device=dev, generator=g2).to(torch.int32).reshape(1, npg).contiguous()
+            prm = B.attn_params(Hq2, Hkv2, 64, 16, npg, "f32")
+            out2 = torch.empty_like(q2)
+            ws2 = torch.empty(B.mc_prefill_attn_workspace_bytes(prm, 1, C2), dtype=torch.uint8, device=dev)
+            s2 = torch.cuda.current_stream()
+            for _ in range(2):
+                B.mc_prefill_attn_paged(prm, q2, k2, v2, bt2, [P2], [C2], out2, None, ws2, s2)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(s2)
+            for _ in range(5):
+                B.mc_prefill_attn_paged(prm, q2, k2, v2, bt2, [P2], [C2], out2, None, ws2, s2)
+            b.record(s2)
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / 5
+            fl = 4 * 64 * Hq2 * (C2 * P2 + C2 * (C2 + 1) // 2)
+            return {"workload": "fp32, 64/8 heads, head_dim 64, P=8192, C=8192", "flops": fl, "ms": round(ms, 3),
+                    "tflops": round(fl / (ms * 1e-3) / 1e12, 1), "peak": 157.3,
+                    "frac_fp32_mfma_peak": round(fl / (ms * 1e-3) / 1e12 / 157.3, 4)}
+
+        result["attn_fp32"] = fp32_attention()
+        torch.cuda.empty_cache()
         # a small chunk against a long prefix (16 new tokens behind 131056 cached ones, 64/8 heads): 8 work
         # items for 256 CUs unless the keys are split
         result["attn_small_chunk"] = whole_vs_split(131056, 16, 64, 8, 20)
