@@ -329,6 +329,9 @@ mc_status mc_kv_store_layer(const void* k_pool_layer, const void* v_pool_layer, 
  *   tok_offsets  host  [batch + 1], request r = tokens[tok_offsets[r] .. tok_offsets[r+1])
  *   keys         dev   uint64, request r's ceil(len_r / block_tokens) keys back to back in request order
  *   workspace    dev   >= mc_prefix_hash_workspace_bytes(batch), 16-byte aligned
+ *
+ * A request of more than 2^26 - 8 blocks is MC_ERR_RANGE; batch == 0 or no tokens at all is MC_OK and
+ * enqueues nothing.
  */
 size_t mc_prefix_hash_workspace_bytes(int32_t batch);
 mc_status mc_prefix_hash(const int32_t* tokens, const int64_t* tok_offsets, int32_t batch, int32_t block_tokens,
