@@ -20,12 +20,16 @@
 //     (lane base XOR constant) + constant.  Tiles that lie wholly inside what every
 //     row of the workgroup may see run a mask-free body; only tiles that touch the
 //     chunk's diagonal compare key index against row position.
-//   * Online softmax in fp32, base 2 (scale * log2 e folded into one fma).  The
-//     running maximum is only raised when a tile exceeds it by more than 2^8, so
-//     the accumulator rescale is rare; any reference below overflow gives the
-//     same quotient O / l.
-//   * Two waves per SIMD: while one wave's softmax occupies the vector ALU the
-//     other wave's MFMAs keep the matrix pipe busy.
+//   * Online softmax in fp32, base 2 (scale * log2 e folded into one fma).  Any
+//     reference below overflow gives the same quotient O / l, so fully visible
+//     blocks take no maxima at all: probabilities are formed against the reference
+//     as it stands, and a block whose probability sums show that a score outgrew it
+//     by more than 2^8 is recomputed against its true maximum (rare; O is rescaled
+//     only then).  Blocks on the chunk's diagonal take the masked, max-first path.
+//   * Two waves per SIMD, half a step apart: while one wave's softmax occupies the
+//     vector ALU under its score MFMAs, the other wave's P V MFMAs keep the matrix
+//     pipe busy.  Waves of the second half whose rows lie past the chunk's end exit
+//     at once (the barriers count surviving waves only).
 #include <type_traits>
 
 #include "mc_internal.h"
