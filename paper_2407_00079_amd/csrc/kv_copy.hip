@@ -8,6 +8,10 @@
 // them for a 32 KiB-page layer) measured best here: slices of 4..32 KiB, 64..1024
 // threads, and persistent grids all land within a few percent of each other, at
 // the rate the HBM sustains for a read+write mix.
+//
+// Also here, all of them byte movers or integer scans over page id lists: the ranking of a page
+// list by pool address (so that the scattered side of a copy can walk the pool front to back),
+// the range check of an id list, and the append of a chunk's new K/V rows into their page slots.
 #include "mc_internal.h"
 
 namespace mc {
