@@ -105,18 +105,27 @@ def main():
             page = self.bt.long()[req, pos // c.page_size]
             self.k_new = self.k[page, :, pos % c.page_size, :].contiguous()
             self.v_new = self.v[page, :, pos % c.page_size, :].contiguous()
-            self.append_ws = torch.empty(B.mc_kv_append_workspace_bytes(c.batch), dtype=torch.uint8, device=dev)
             if args.zero_inputs:
                 for t in (self.q, self.k, self.v, self.k_new, self.v_new):
                     t.zero_()
 
+            # work list and request table: prepared and uploaded once per batch, as a prefill pass would for all of
+            # its layers; append and attention of every step then only launch their kernels
+            self.plan = B.mc_prefill_attn_prepare(self.params, self.pl, self.nl, 0, self.ws)
+            self.ws_one_shot = torch.empty_like(self.ws)
+            torch.cuda.synchronize()          # the upload has landed before any stream runs from the plan
+
         def append(self, stream):
-            B.mc_kv_append_paged(self.params, self.k_new, self.v_new, self.k, self.v, self.bt, self.pl, self.nl,
-                                 self.append_ws, stream)
+            B.mc_kv_append_run(self.params, self.plan, self.k_new, self.v_new, self.k, self.v, self.bt, self.ws, stream)
 
         def launch(self, stream):
+            B.mc_prefill_attn_run(self.params, self.plan, self.q, self.k, self.v, self.bt, self.out, self.lse, self.ws,
+                                  stream)
+
+        def launch_one_shot(self, stream):
+            # the same attention through the call that builds and uploads its work list itself
             B.mc_prefill_attn_paged(self.params, self.q, self.k, self.v, self.bt, self.pl, self.nl, self.out,
-                                    self.lse, self.ws, stream)
+                                    self.lse, self.ws_one_shot, stream)
 
         def time_isolated(self, iters=20, warm=5):
             s = torch.cuda.current_stream()
@@ -234,7 +243,8 @@ def main():
         "config": {"workload": f"config {args.attn_config} attention "
                                f"(P={attn.pl if len(attn.pl) < 3 else 'varlen'}, C={attn.nl if len(attn.nl) < 3 else 'varlen'}, "
                                f"{attn.case.num_q_heads}/{attn.case.num_kv_heads} heads, D=128, 16-token pages) "
-                               f"preceded by the append of its chunk's K/V rows, "
+                               f"preceded by the append of its chunk's K/V rows (work list prepared once per batch: "
+                               f"mc_prefill_attn_prepare, then mc_kv_append_run + mc_prefill_attn_run per step), "
                                f"+ one config-5 layer of KV unpack and pack (2048 pages x 32 KiB, K and V) on a second stream",
                    "attn_flops_per_step": attn.flops, "copy_bytes_per_step": 2 * copy_bytes},
         "pct_mfma_peak": round(100 * value / MFMA_BF16_PEAK_TFLOPS, 2),
@@ -262,6 +272,18 @@ def main():
                                    "tflops": round(attn.flops / (med * 1e-3) / 1e12, 2),
                                    "pct_mfma_peak": round(100 * attn.flops / (med * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2)}
         s = torch.cuda.current_stream()
+        # the one-shot call (list built and uploaded inside every call), back to back like the isolated runs
+        for _ in range(3):
+            attn.launch_one_shot(s)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(s)
+        for _ in range(10):
+            attn.launch_one_shot(s)
+        b.record(s)
+        torch.cuda.synchronize()
+        result["attn_one_shot_call"] = {"ms_per_call_back_to_back": round(a.elapsed_time(b) / 10, 4),
+                                        "what": "mc_prefill_attn_paged: prepare + run in one call"}
+
         def pack_ordered(l, stream):
             B.mc_kv_pack_layer_ordered(k_pool[l], v_pool[l], N2, pb, dst_ids, order, n, k_store[l], v_store[l], stream)
 

@@ -153,6 +153,50 @@ int32_t mc_prefill_attn_suggest_kv_splits(const mc_attn_params* p, const int32_t
                                           const int32_t* new_lens, int32_t batch);
 
 /*
+ * Prepare once, run per layer.  The work list and the request table depend on the lengths of the
+ * batch only, and a prefill pass makes the same attention and append calls for every layer of
+ * the model (Section 5.2: layer-wise prefill): mc_prefill_attn_prepare builds them and enqueues
+ * their upload into the workspace ONCE; the run calls then only launch kernels - no host
+ * work beyond argument checks, no upload, and nothing a stream capture could not record.
+ *
+ *   kv_splits  0: plan for mc_prefill_attn_run;  1 .. MC_MAX_KV_SPLITS: for mc_prefill_attn_run_split
+ *   workspace  dev  >= mc_prefill_attn_workspace_bytes(...) (kv_splits == 0) or
+ *                   >= mc_prefill_attn_split_workspace_bytes(...); the runs read it, so it must
+ *                   keep its bytes for as long as the plan is in use, and the runs must be
+ *                   ordered after the prepare call (same stream, or an event)
+ *   plan       HOST out: plain data the run calls take back; valid with these params only
+ *
+ * The run calls compute exactly what mc_prefill_attn_paged / mc_prefill_attn_paged_split /
+ * mc_kv_append_paged compute for the lengths the plan was prepared with (those calls are
+ * prepare + run in one), with the same argument rules; block tables need at least
+ * plan->need_pages columns.  A plan for no new tokens is empty and its runs enqueue nothing.
+ * mc_kv_append_run takes either form of plan.
+ */
+typedef struct {
+  int32_t n_items;            /* work items (workgroups) of the attention launch */
+  int32_t batch;
+  int32_t kv_splits;          /* 0 = whole-row form */
+  int32_t need_pages;         /* most pages any request with new tokens spans */
+  int64_t total_new_tokens;
+  int64_t reqs_offset;        /* byte offset of the request table in the workspace */
+  int32_t num_q_heads, num_kv_heads, dtype, reserved;   /* of the params it was prepared with */
+} mc_attn_plan;
+
+mc_status mc_prefill_attn_prepare(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens,
+                                  int32_t batch, int32_t kv_splits, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream, mc_attn_plan* plan);
+mc_status mc_prefill_attn_run(const mc_attn_params* p, const mc_attn_plan* plan, const void* q, const void* k_pool,
+                              const void* v_pool, const int32_t* block_tables, int32_t max_pages_per_req, void* out,
+                              float* lse, const void* workspace, void* hip_stream);
+mc_status mc_prefill_attn_run_split(const mc_attn_params* p, const mc_attn_plan* plan, const void* q,
+                                    const void* k_pool, const void* v_pool, const int32_t* block_tables,
+                                    int32_t max_pages_per_req, float* o_parts, float* lse_parts,
+                                    const void* workspace, void* hip_stream);
+mc_status mc_kv_append_run(const mc_attn_params* p, const mc_attn_plan* plan, const void* k_new, const void* v_new,
+                           void* k_pool, void* v_pool, const int32_t* block_tables, int32_t max_pages_per_req,
+                           const void* workspace, void* hip_stream);
+
+/*
  * The work list the two attention calls above launch for these lengths, in launch order, written
  * to HOST memory - for inspection and for tests of the host logic; no GPU call, nothing enqueued.
  * One work item = one workgroup = one tile of 256 stacked query rows (row = token * G + head in

@@ -24,7 +24,8 @@ EXPORTS = ("mc_status_string", "mc_prefill_attn_workspace_bytes", "mc_prefill_at
            "mc_kv_load_layer", "mc_kv_store_layer", "mc_prefix_hash_workspace_bytes", "mc_prefix_hash",
            "mc_prefix_match_workspace_bytes", "mc_prefix_match", "mc_kv_page_order", "mc_kv_pack_layer_ordered",
            "mc_kv_unpack_layer_ordered", "mc_prefill_attn_suggest_kv_splits", "mc_kv_check_page_ids",
-           "mc_prefill_attn_plan")
+           "mc_prefill_attn_plan", "mc_prefill_attn_prepare", "mc_prefill_attn_run", "mc_prefill_attn_run_split",
+           "mc_kv_append_run")
 MC_MAX_KV_SPLITS = 256
 
 
@@ -33,6 +34,13 @@ class McAttnParams(ctypes.Structure):
                 ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32),
                 ("num_pages", ctypes.c_int64), ("dtype", ctypes.c_int32),
                 ("softmax_scale", ctypes.c_float)]
+
+
+class McAttnPlan(ctypes.Structure):
+    _fields_ = [("n_items", ctypes.c_int32), ("batch", ctypes.c_int32), ("kv_splits", ctypes.c_int32),
+                ("need_pages", ctypes.c_int32), ("total_new_tokens", ctypes.c_int64), ("reqs_offset", ctypes.c_int64),
+                ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 class McError(RuntimeError):
@@ -80,6 +88,15 @@ def lib():
                                          ctypes.c_size_t, vp]
         l.mc_prefill_attn_split_workspace_bytes.restype = ctypes.c_size_t
         l.mc_prefill_attn_split_workspace_bytes.argtypes = [ctypes.POINTER(McAttnParams), i32, i64, i32]
+        pp, pl_ = ctypes.POINTER(McAttnParams), ctypes.POINTER(McAttnPlan)
+        l.mc_prefill_attn_prepare.restype = ctypes.c_int
+        l.mc_prefill_attn_prepare.argtypes = [pp, vp, vp, i32, i32, vp, ctypes.c_size_t, vp, pl_]
+        l.mc_prefill_attn_run.restype = ctypes.c_int
+        l.mc_prefill_attn_run.argtypes = [pp, pl_, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+        l.mc_prefill_attn_run_split.restype = ctypes.c_int
+        l.mc_prefill_attn_run_split.argtypes = [pp, pl_, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+        l.mc_kv_append_run.restype = ctypes.c_int
+        l.mc_kv_append_run.argtypes = [pp, pl_, vp, vp, vp, vp, vp, i32, vp, vp]
         l.mc_prefill_attn_plan.restype = ctypes.c_int
         l.mc_prefill_attn_plan.argtypes = [ctypes.POINTER(McAttnParams), vp, vp, i32, i32, vp, i64, vp]
         l.mc_prefill_attn_suggest_kv_splits.restype = ctypes.c_int32
@@ -156,6 +173,54 @@ def mc_prefill_attn_paged(params: McAttnParams, q, k_pool, v_pool, block_tables,
 def mc_prefill_attn_split_workspace_bytes(params: McAttnParams, batch: int, total_new_tokens: int,
                                           kv_splits: int) -> int:
     return int(lib().mc_prefill_attn_split_workspace_bytes(ctypes.byref(params), batch, total_new_tokens, kv_splits))
+
+
+def _max_pages(block_tables) -> int:
+    return int(block_tables.shape[1]) if block_tables is not None and block_tables.dim() == 2 else 0
+
+
+def mc_prefill_attn_prepare(params: McAttnParams, prefix_lens, new_lens, kv_splits: int, workspace,
+                            stream=None) -> McAttnPlan:
+    """Build and upload the work list and request table of a batch ONCE; the returned plan drives any number of
+    mc_prefill_attn_run / mc_prefill_attn_run_split / mc_kv_append_run calls (one per layer) on the same workspace."""
+    batch = len(prefix_lens)
+    pl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in prefix_lens])
+    nl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in new_lens])
+    ws_bytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    plan = McAttnPlan()
+    st = int(lib().mc_prefill_attn_prepare(ctypes.byref(params), pl, nl, batch, kv_splits, _dev_ptr(workspace), ws_bytes,
+                                           _stream_handle(stream), ctypes.byref(plan)))
+    if st != MC_OK:
+        raise McError(st, "mc_prefill_attn_prepare")
+    return plan
+
+
+def mc_prefill_attn_run(params: McAttnParams, plan: McAttnPlan, q, k_pool, v_pool, block_tables, out, lse, workspace,
+                        stream=None) -> None:
+    st = int(lib().mc_prefill_attn_run(ctypes.byref(params), ctypes.byref(plan), _dev_ptr(q), _dev_ptr(k_pool),
+                                       _dev_ptr(v_pool), _dev_ptr(block_tables), _max_pages(block_tables),
+                                       _dev_ptr(out), _dev_ptr(lse), _dev_ptr(workspace), _stream_handle(stream)))
+    if st != MC_OK:
+        raise McError(st, "mc_prefill_attn_run")
+
+
+def mc_prefill_attn_run_split(params: McAttnParams, plan: McAttnPlan, q, k_pool, v_pool, block_tables, o_parts,
+                              lse_parts, workspace, stream=None) -> None:
+    st = int(lib().mc_prefill_attn_run_split(ctypes.byref(params), ctypes.byref(plan), _dev_ptr(q), _dev_ptr(k_pool),
+                                             _dev_ptr(v_pool), _dev_ptr(block_tables), _max_pages(block_tables),
+                                             _dev_ptr(o_parts), _dev_ptr(lse_parts), _dev_ptr(workspace),
+                                             _stream_handle(stream)))
+    if st != MC_OK:
+        raise McError(st, "mc_prefill_attn_run_split")
+
+
+def mc_kv_append_run(params: McAttnParams, plan: McAttnPlan, k_new, v_new, k_pool, v_pool, block_tables, workspace,
+                     stream=None) -> None:
+    st = int(lib().mc_kv_append_run(ctypes.byref(params), ctypes.byref(plan), _dev_ptr(k_new), _dev_ptr(v_new),
+                                    _dev_ptr(k_pool), _dev_ptr(v_pool), _dev_ptr(block_tables),
+                                    _max_pages(block_tables), _dev_ptr(workspace), _stream_handle(stream)))
+    if st != MC_OK:
+        raise McError(st, "mc_kv_append_run")
 
 
 def mc_prefill_attn_plan(params: McAttnParams, prefix_lens, new_lens, kv_splits: int = 0):

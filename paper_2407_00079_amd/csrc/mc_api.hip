@@ -194,51 +194,63 @@ void build_work_list(const mc_attn_params* p, const int32_t* prefix_lens, const 
   }
 }
 
-// kv_splits == 0: the whole-row kernel writes out / lse.  kv_splits >= 1: the split kernel writes
-// partials (out / lse unused).
-mc_status attn_enqueue(const mc_attn_params* p, const void* q, const void* k_pool, const void* v_pool,
-                       const int32_t* block_tables, int32_t max_pages_per_req, const int32_t* prefix_lens,
-                       const int32_t* new_lens, int32_t batch, void* out, float* lse, int32_t kv_splits,
-                       float* o_parts, float* lse_parts, void* workspace, size_t workspace_bytes,
-                       void* hip_stream) {
-  const bool split = kv_splits > 0;
-  mc_status st = check_params(p);
-  if (st != MC_OK) return st;
-  if (batch < 0 || max_pages_per_req < 0) return MC_ERR_SHAPE;
-  if (batch == 0) return MC_OK;
-  if (prefix_lens == nullptr || new_lens == nullptr) return MC_ERR_NULL;
-
-  int64_t total_new = 0;
+// Lengths of a batch: sign and range checks, sum of the new tokens, most pages any request
+// with new tokens needs.
+mc_status check_lens(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch,
+                     int64_t* total_new, int32_t* need_pages) {
+  *total_new = 0;
+  *need_pages = 0;
   for (int32_t r = 0; r < batch; ++r) {
     if (prefix_lens[r] < 0 || new_lens[r] < 0) return MC_ERR_SHAPE;
     const int64_t len = (int64_t)prefix_lens[r] + new_lens[r];
     if (len > INT32_MAX - 1024) return MC_ERR_RANGE;
-    if (new_lens[r] > 0 && (int64_t)max_pages_per_req * p->page_size < len) return MC_ERR_SHAPE;
-    total_new += new_lens[r];
+    if (new_lens[r] > 0) {
+      const int32_t pages = (int32_t)((len + p->page_size - 1) / p->page_size);
+      *need_pages = pages > *need_pages ? pages : *need_pages;
+    }
+    *total_new += new_lens[r];
   }
-  if (total_new == 0) return MC_OK;
+  return MC_OK;
+}
+
+// Everything an attention launch checks besides the lengths.  kv_splits == 0: the whole-row kernel
+// writes out / lse.  kv_splits >= 1: the split kernel writes partials (out / lse unused).
+mc_status check_attn_buffers(bool split, const void* q, const void* k_pool, const void* v_pool,
+                             const int32_t* block_tables, int32_t batch, int32_t max_pages_per_req, int32_t need_pages,
+                             const void* out, const float* lse, const float* o_parts, const float* lse_parts,
+                             const void* workspace) {
+  if (max_pages_per_req < need_pages) return MC_ERR_SHAPE;
   if (q == nullptr || k_pool == nullptr || v_pool == nullptr || block_tables == nullptr) return MC_ERR_NULL;
   if (split ? (o_parts == nullptr || lse_parts == nullptr) : out == nullptr) return MC_ERR_NULL;
   if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out) || !aligned16(workspace) ||
       !aligned16(o_parts) || (reinterpret_cast<uintptr_t>(block_tables) & 3u) ||
       (reinterpret_cast<uintptr_t>(lse) & 3u) || (reinterpret_cast<uintptr_t>(lse_parts) & 3u))
     return MC_ERR_ALIGN;
-  const int G = p->num_q_heads / p->num_kv_heads;
-  if (total_new * p->num_q_heads > INT32_MAX || (int64_t)batch * max_pages_per_req > INT32_MAX) return MC_ERR_RANGE;
+  if ((int64_t)batch * max_pages_per_req > INT32_MAX) return MC_ERR_RANGE;
+  return MC_OK;
+}
+
+// Build the work list and the request table of a batch and enqueue their upload into the
+// workspace; fill `plan` with what a later launch needs to know on the host.  The lengths have
+// passed check_lens and total_new > 0.
+mc_status prepare_attn(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch,
+                       int32_t kv_splits, int64_t total_new, int32_t need_pages, void* workspace,
+                       size_t workspace_bytes, hipStream_t stream, mc_attn_plan* plan) {
+  const bool split = kv_splits > 0;
+  if (total_new * p->num_q_heads > INT32_MAX) return MC_ERR_RANGE;
   const size_t n_max = max_items(p, batch, total_new, split ? kv_splits : 1);
   if (n_max > (size_t)INT32_MAX) return MC_ERR_RANGE;
   if (workspace == nullptr ||
       workspace_bytes < sizeof(mc::AttnItem) * n_max + sizeof(mc::AttnReq) * (size_t)batch + 64)
     return MC_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return MC_ERR_ALIGN;
 
   std::vector<mc::AttnReq> reqs;
   std::vector<mc::AttnItem> items;
   build_work_list(p, prefix_lens, new_lens, batch, split ? kv_splits : 0, reqs, items);
   const size_t n_items = items.size();
 
-  // ---- upload work list + request table into the caller's workspace (one pinned, async copy)
-  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-  char* ws = reinterpret_cast<char*>(workspace);
+  // one pinned, asynchronous copy of work list + request table
   const size_t items_bytes = sizeof(mc::AttnItem) * n_items;
   const size_t reqs_off = (items_bytes + 15) & ~(size_t)15;
   const size_t up_bytes = reqs_off + sizeof(mc::AttnReq) * reqs.size();
@@ -247,9 +259,27 @@ mc_status attn_enqueue(const mc_attn_params* p, const void* q, const void* k_poo
   if (host == nullptr) return MC_ERR_HIP;
   std::memcpy(host, items.data(), items_bytes);
   std::memcpy(host + reqs_off, reqs.data(), sizeof(mc::AttnReq) * reqs.size());
-  if (hipMemcpyAsync(ws, host, up_bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
+  if (hipMemcpyAsync(workspace, host, up_bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
   if (!g_staging.release_after(slot, stream)) return MC_ERR_HIP;
 
+  plan->n_items = (int32_t)n_items;
+  plan->batch = batch;
+  plan->kv_splits = split ? kv_splits : 0;
+  plan->need_pages = need_pages;
+  plan->total_new_tokens = total_new;
+  plan->reqs_offset = (int64_t)reqs_off;
+  plan->num_q_heads = p->num_q_heads;
+  plan->num_kv_heads = p->num_kv_heads;
+  plan->dtype = (int32_t)p->dtype;
+  plan->reserved = 0;
+  return MC_OK;
+}
+
+mc_status launch_planned_attn(const mc_attn_params* p, const mc_attn_plan* plan, const void* q, const void* k_pool,
+                              const void* v_pool, const int32_t* block_tables, int32_t max_pages_per_req, void* out,
+                              float* lse, float* o_parts, float* lse_parts, const void* workspace,
+                              hipStream_t stream) {
+  const char* ws = reinterpret_cast<const char*>(workspace);
   mc::AttnArgs args;
   args.q = q;
   args.k_pool = k_pool;
@@ -258,19 +288,58 @@ mc_status attn_enqueue(const mc_attn_params* p, const void* q, const void* k_poo
   args.out = out;
   args.lse = lse;
   args.items = reinterpret_cast<const mc::AttnItem*>(ws);
-  args.reqs = reinterpret_cast<const mc::AttnReq*>(ws + reqs_off);
+  args.reqs = reinterpret_cast<const mc::AttnReq*>(ws + plan->reqs_offset);
   args.Hq = p->num_q_heads;
   args.Hkv = p->num_kv_heads;
-  args.G = G;
+  args.G = p->num_q_heads / p->num_kv_heads;
   args.max_pages = max_pages_per_req;
   const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale : 1.0 / std::sqrt((double)p->head_dim);
   args.scale_log2e = (float)(scale * 1.4426950408889634);
-  args.n_items = (int32_t)n_items;
-  args.kv_splits = split ? kv_splits : 0;
-  args.rows_total = total_new * p->num_q_heads;
+  args.n_items = plan->n_items;
+  args.kv_splits = plan->kv_splits;
+  args.rows_total = plan->total_new_tokens * p->num_q_heads;
   args.o_parts = o_parts;
   args.lse_parts = lse_parts;
   if (mc::launch_attn(p->dtype, args, stream) != hipSuccess) return MC_ERR_HIP;
+  return MC_OK;
+}
+
+// One-shot form: every check first (a rejected call enqueues nothing), then upload and launch.
+mc_status attn_enqueue(const mc_attn_params* p, const void* q, const void* k_pool, const void* v_pool,
+                       const int32_t* block_tables, int32_t max_pages_per_req, const int32_t* prefix_lens,
+                       const int32_t* new_lens, int32_t batch, void* out, float* lse, int32_t kv_splits,
+                       float* o_parts, float* lse_parts, void* workspace, size_t workspace_bytes,
+                       void* hip_stream) {
+  mc_status st = check_params(p);
+  if (st != MC_OK) return st;
+  if (batch < 0 || max_pages_per_req < 0) return MC_ERR_SHAPE;
+  if (batch == 0) return MC_OK;
+  if (prefix_lens == nullptr || new_lens == nullptr) return MC_ERR_NULL;
+  int64_t total_new = 0;
+  int32_t need_pages = 0;
+  st = check_lens(p, prefix_lens, new_lens, batch, &total_new, &need_pages);
+  if (st != MC_OK) return st;
+  if (total_new == 0) return MC_OK;
+  st = check_attn_buffers(kv_splits > 0, q, k_pool, v_pool, block_tables, batch, max_pages_per_req, need_pages, out,
+                          lse, o_parts, lse_parts, workspace);
+  if (st != MC_OK) return st;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  mc_attn_plan plan;
+  st = prepare_attn(p, prefix_lens, new_lens, batch, kv_splits, total_new, need_pages, workspace, workspace_bytes,
+                    stream, &plan);
+  if (st != MC_OK) return st;
+  return launch_planned_attn(p, &plan, q, k_pool, v_pool, block_tables, max_pages_per_req, out, lse, o_parts,
+                             lse_parts, workspace, stream);
+}
+
+// A plan handed back by the caller: made for these params, of the wanted form, not empty.
+mc_status check_plan(const mc_attn_params* p, const mc_attn_plan* plan, bool want_split) {
+  if (plan == nullptr) return MC_ERR_NULL;
+  if (plan->num_q_heads != p->num_q_heads || plan->num_kv_heads != p->num_kv_heads || plan->dtype != (int32_t)p->dtype ||
+      plan->n_items < 0 || plan->batch < 0 || plan->total_new_tokens < 0 || plan->reqs_offset < 0 ||
+      (plan->reqs_offset & 15) != 0 || plan->kv_splits < 0 || plan->kv_splits > MC_MAX_KV_SPLITS)
+    return MC_ERR_SHAPE;
+  if (want_split != (plan->kv_splits > 0)) return MC_ERR_SHAPE;
   return MC_OK;
 }
 
@@ -302,6 +371,90 @@ mc_status mc_prefill_attn_paged_split(const mc_attn_params* p, const void* q, co
   if (kv_splits < 1 || kv_splits > MC_MAX_KV_SPLITS) return MC_ERR_SHAPE;
   return attn_enqueue(p, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens, batch, nullptr,
                       nullptr, kv_splits, o_parts, lse_parts, workspace, workspace_bytes, hip_stream);
+}
+
+mc_status mc_prefill_attn_prepare(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens,
+                                  int32_t batch, int32_t kv_splits, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream, mc_attn_plan* plan) {
+  mc_status st = check_params(p);
+  if (st != MC_OK) return st;
+  if (batch < 0 || kv_splits < 0 || kv_splits > MC_MAX_KV_SPLITS) return MC_ERR_SHAPE;
+  if (plan == nullptr || (batch > 0 && (prefix_lens == nullptr || new_lens == nullptr))) return MC_ERR_NULL;
+  int64_t total_new = 0;
+  int32_t need_pages = 0;
+  st = check_lens(p, prefix_lens, new_lens, batch, &total_new, &need_pages);
+  if (st != MC_OK) return st;
+  if (total_new == 0) {
+    // nothing to launch: an empty plan, nothing uploaded
+    *plan = mc_attn_plan{0, batch, kv_splits, 0, 0, 0, p->num_q_heads, p->num_kv_heads, (int32_t)p->dtype, 0};
+    return MC_OK;
+  }
+  return prepare_attn(p, prefix_lens, new_lens, batch, kv_splits, total_new, need_pages, workspace, workspace_bytes,
+                      reinterpret_cast<hipStream_t>(hip_stream), plan);
+}
+
+mc_status mc_prefill_attn_run(const mc_attn_params* p, const mc_attn_plan* plan, const void* q, const void* k_pool,
+                              const void* v_pool, const int32_t* block_tables, int32_t max_pages_per_req, void* out,
+                              float* lse, const void* workspace, void* hip_stream) {
+  mc_status st = check_params(p);
+  if (st != MC_OK) return st;
+  st = check_plan(p, plan, false);
+  if (st != MC_OK) return st;
+  if (max_pages_per_req < 0) return MC_ERR_SHAPE;
+  if (plan->n_items == 0) return MC_OK;
+  st = check_attn_buffers(false, q, k_pool, v_pool, block_tables, plan->batch, max_pages_per_req, plan->need_pages,
+                          out, lse, nullptr, nullptr, workspace);
+  if (st != MC_OK) return st;
+  if (workspace == nullptr) return MC_ERR_WORKSPACE;
+  return launch_planned_attn(p, plan, q, k_pool, v_pool, block_tables, max_pages_per_req, out, lse, nullptr, nullptr,
+                             workspace, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+mc_status mc_prefill_attn_run_split(const mc_attn_params* p, const mc_attn_plan* plan, const void* q,
+                                    const void* k_pool, const void* v_pool, const int32_t* block_tables,
+                                    int32_t max_pages_per_req, float* o_parts, float* lse_parts,
+                                    const void* workspace, void* hip_stream) {
+  mc_status st = check_params(p);
+  if (st != MC_OK) return st;
+  st = check_plan(p, plan, true);
+  if (st != MC_OK) return st;
+  if (max_pages_per_req < 0) return MC_ERR_SHAPE;
+  if (plan->n_items == 0) return MC_OK;
+  st = check_attn_buffers(true, q, k_pool, v_pool, block_tables, plan->batch, max_pages_per_req, plan->need_pages,
+                          nullptr, nullptr, o_parts, lse_parts, workspace);
+  if (st != MC_OK) return st;
+  if (workspace == nullptr) return MC_ERR_WORKSPACE;
+  return launch_planned_attn(p, plan, q, k_pool, v_pool, block_tables, max_pages_per_req, nullptr, nullptr, o_parts,
+                             lse_parts, workspace, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+mc_status mc_kv_append_run(const mc_attn_params* p, const mc_attn_plan* plan, const void* k_new, const void* v_new,
+                           void* k_pool, void* v_pool, const int32_t* block_tables, int32_t max_pages_per_req,
+                           const void* workspace, void* hip_stream) {
+  mc_status st = check_params(p);
+  if (st != MC_OK) return st;
+  if (plan == nullptr) return MC_ERR_NULL;
+  st = check_plan(p, plan, plan->kv_splits > 0);       // either form of plan holds the request table
+  if (st != MC_OK) return st;
+  if (max_pages_per_req < 0) return MC_ERR_SHAPE;
+  if (plan->n_items == 0) return MC_OK;
+  if (max_pages_per_req < plan->need_pages) return MC_ERR_SHAPE;
+  if (k_new == nullptr || v_new == nullptr || k_pool == nullptr || v_pool == nullptr || block_tables == nullptr)
+    return MC_ERR_NULL;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(workspace) ||
+      (reinterpret_cast<uintptr_t>(block_tables) & 3u))
+    return MC_ERR_ALIGN;
+  const int64_t total_new = plan->total_new_tokens;
+  if (total_new > INT32_MAX || total_new * p->num_kv_heads * 16 / 256 + 1 > INT32_MAX ||
+      (int64_t)plan->batch * max_pages_per_req > INT32_MAX)
+    return MC_ERR_RANGE;
+  if (workspace == nullptr) return MC_ERR_WORKSPACE;
+  const char* ws = reinterpret_cast<const char*>(workspace);
+  if (mc::launch_kv_append(k_new, v_new, k_pool, v_pool, block_tables, max_pages_per_req,
+                           reinterpret_cast<const mc::AttnReq*>(ws + plan->reqs_offset), plan->batch, total_new,
+                           p->num_kv_heads, reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return MC_ERR_HIP;
+  return MC_OK;
 }
 
 mc_status mc_prefill_attn_plan(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens,

@@ -145,3 +145,39 @@ def test_suggested_key_slices(lib):
     bad = good_params()
     bad.head_dim = 77
     assert s(bad, [100], [16]) == 0
+
+
+def test_prepare_and_run_host_side(lib):
+    """What prepare / run decide without touching the GPU: empty plans, plans that do not fit the call."""
+    p = good_params()
+
+    def prepare(prefix, new, kv_splits, ws=None, ws_bytes=0):
+        pl, nl = (ctypes.c_int32 * len(prefix))(*prefix), (ctypes.c_int32 * len(new))(*new)
+        out = B.McAttnPlan()
+        st = lib.mc_prefill_attn_prepare(ctypes.byref(p), pl, nl, len(prefix), kv_splits, ws, ws_bytes, None,
+                                         ctypes.byref(out))
+        return st, out
+
+    st, plan = prepare([100, 7], [0, 0], 0)                      # no new tokens: empty plan, no workspace needed
+    assert st == B.MC_OK
+    assert (plan.n_items, plan.batch, plan.total_new_tokens, plan.kv_splits) == (0, 2, 0, 0)
+    run = lib.mc_prefill_attn_run
+    assert run(ctypes.byref(p), ctypes.byref(plan), None, None, None, None, 0, None, None, None, None) == B.MC_OK
+    assert lib.mc_kv_append_run(ctypes.byref(p), ctypes.byref(plan), None, None, None, None, None, 0, None, None) == B.MC_OK
+    # a plan is tied to the head counts and dtype it was prepared with, and to its form
+    other = B.attn_params(32, 8, 128, 16, 4096, "bf16")
+    assert run(ctypes.byref(other), ctypes.byref(plan), None, None, None, None, 0, None, None, None, None) == B.MC_ERR_SHAPE
+    assert lib.mc_prefill_attn_run_split(ctypes.byref(p), ctypes.byref(plan), None, None, None, None, 0, None, None, None,
+                                         None) == B.MC_ERR_SHAPE
+    assert run(ctypes.byref(p), None, None, None, None, None, 0, None, None, None, None) == B.MC_ERR_NULL
+    # a plan with work in it (filled in by hand here: no upload happens in this test) is checked against the buffers
+    full = B.McAttnPlan(2048, 1, 0, 1024, 8192, 32768, 64, 8, B.MC_DTYPE_BF16, 0)
+    assert run(ctypes.byref(p), ctypes.byref(full), FAKE, FAKE, FAKE, FAKE, 1000, FAKE, None, FAKE, None) == B.MC_ERR_SHAPE
+    assert run(ctypes.byref(p), ctypes.byref(full), None, FAKE, FAKE, FAKE, 1024, FAKE, None, FAKE, None) == B.MC_ERR_NULL
+    assert run(ctypes.byref(p), ctypes.byref(full), FAKE + 4, FAKE, FAKE, FAKE, 1024, FAKE, None, FAKE, None) == B.MC_ERR_ALIGN
+    assert run(ctypes.byref(p), ctypes.byref(full), FAKE, FAKE, FAKE, FAKE, 1024, FAKE, None, None, None) == B.MC_ERR_WORKSPACE
+    # prepare: bad lengths and a missing workspace are refused before any GPU call
+    assert prepare([-1], [5], 0)[0] == B.MC_ERR_SHAPE
+    assert prepare([8192], [8192], 0)[0] == B.MC_ERR_WORKSPACE
+    assert prepare([8192], [8192], 0, FAKE, 64)[0] == B.MC_ERR_WORKSPACE
+    assert prepare([8192], [8192], B.MC_MAX_KV_SPLITS + 1)[0] == B.MC_ERR_SHAPE
