@@ -153,6 +153,24 @@ int32_t mc_prefill_attn_suggest_kv_splits(const mc_attn_params* p, const int32_t
                                           const int32_t* new_lens, int32_t batch);
 
 /*
+ * mc_prefill_attn_paged with the choice between the whole-row form and key slices + merge made
+ * by the library: it takes the slice count mc_prefill_attn_suggest_kv_splits gives for the
+ * lengths and, when that is above 1, runs mc_prefill_attn_paged_split and mc_attn_merge_lse on
+ * partial buffers it places in the workspace.  Same arguments, same result (to the tolerance of
+ * the two forms) as mc_prefill_attn_paged; the workspace is larger:
+ *
+ *   workspace  dev  >= mc_prefill_attn_auto_workspace_bytes(...) for the same params and lengths
+ *                   (work list + request table + kv_splits * rows * (head_dim + 1) floats),
+ *                   16-byte aligned; 0 is returned for arguments the call would reject
+ */
+size_t mc_prefill_attn_auto_workspace_bytes(const mc_attn_params* p, const int32_t* prefix_lens,
+                                            const int32_t* new_lens, int32_t batch);
+mc_status mc_prefill_attn_auto(const mc_attn_params* p, const void* q, const void* k_pool, const void* v_pool,
+                               const int32_t* block_tables, int32_t max_pages_per_req,
+                               const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch, void* out,
+                               float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Prepare once, run per layer.  The work list and the request table depend on the lengths of the
  * batch only, and a prefill pass makes the same attention and append calls for every layer of
  * the model (Section 5.2: layer-wise prefill): mc_prefill_attn_prepare builds them and enqueues

@@ -25,7 +25,7 @@ EXPORTS = ("mc_status_string", "mc_prefill_attn_workspace_bytes", "mc_prefill_at
            "mc_prefix_match_workspace_bytes", "mc_prefix_match", "mc_kv_page_order", "mc_kv_pack_layer_ordered",
            "mc_kv_unpack_layer_ordered", "mc_prefill_attn_suggest_kv_splits", "mc_kv_check_page_ids",
            "mc_prefill_attn_plan", "mc_prefill_attn_prepare", "mc_prefill_attn_run", "mc_prefill_attn_run_split",
-           "mc_kv_append_run")
+           "mc_kv_append_run", "mc_prefill_attn_auto_workspace_bytes", "mc_prefill_attn_auto")
 MC_MAX_KV_SPLITS = 256
 
 
@@ -89,6 +89,10 @@ def lib():
         l.mc_prefill_attn_split_workspace_bytes.restype = ctypes.c_size_t
         l.mc_prefill_attn_split_workspace_bytes.argtypes = [ctypes.POINTER(McAttnParams), i32, i64, i32]
         pp, pl_ = ctypes.POINTER(McAttnParams), ctypes.POINTER(McAttnPlan)
+        l.mc_prefill_attn_auto_workspace_bytes.restype = ctypes.c_size_t
+        l.mc_prefill_attn_auto_workspace_bytes.argtypes = [pp, vp, vp, i32]
+        l.mc_prefill_attn_auto.restype = ctypes.c_int
+        l.mc_prefill_attn_auto.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp]
         l.mc_prefill_attn_prepare.restype = ctypes.c_int
         l.mc_prefill_attn_prepare.argtypes = [pp, vp, vp, i32, i32, vp, ctypes.c_size_t, vp, pl_]
         l.mc_prefill_attn_run.restype = ctypes.c_int
@@ -173,6 +177,31 @@ def mc_prefill_attn_paged(params: McAttnParams, q, k_pool, v_pool, block_tables,
 def mc_prefill_attn_split_workspace_bytes(params: McAttnParams, batch: int, total_new_tokens: int,
                                           kv_splits: int) -> int:
     return int(lib().mc_prefill_attn_split_workspace_bytes(ctypes.byref(params), batch, total_new_tokens, kv_splits))
+
+
+def _lens(prefix_lens, new_lens):
+    batch = len(prefix_lens)
+    pl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in prefix_lens])
+    nl = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in new_lens])
+    return batch, pl, nl
+
+
+def mc_prefill_attn_auto_workspace_bytes(params: McAttnParams, prefix_lens, new_lens) -> int:
+    batch, pl, nl = _lens(prefix_lens, new_lens)
+    return int(lib().mc_prefill_attn_auto_workspace_bytes(ctypes.byref(params), pl, nl, batch))
+
+
+def mc_prefill_attn_auto(params: McAttnParams, q, k_pool, v_pool, block_tables, prefix_lens, new_lens, out, lse,
+                         workspace, stream=None) -> None:
+    """mc_prefill_attn_paged with the whole-row / key-slices choice made by the library (larger workspace)."""
+    batch, pl, nl = _lens(prefix_lens, new_lens)
+    ws_bytes = 0 if workspace is None else int(workspace.numel() * workspace.element_size())
+    max_pages = int(block_tables.shape[1]) if block_tables is not None and block_tables.dim() == 2 else 0
+    st = int(lib().mc_prefill_attn_auto(ctypes.byref(params), _dev_ptr(q), _dev_ptr(k_pool), _dev_ptr(v_pool),
+                                        _dev_ptr(block_tables), max_pages, pl, nl, batch, _dev_ptr(out), _dev_ptr(lse),
+                                        _dev_ptr(workspace), ws_bytes, _stream_handle(stream)))
+    if st != MC_OK:
+        raise McError(st, "mc_prefill_attn_auto")
 
 
 def _max_pages(block_tables) -> int:

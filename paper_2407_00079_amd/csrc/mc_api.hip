@@ -373,6 +373,65 @@ mc_status mc_prefill_attn_paged_split(const mc_attn_params* p, const void* q, co
                       nullptr, kv_splits, o_parts, lse_parts, workspace, workspace_bytes, hip_stream);
 }
 
+namespace {
+// Workspace of the automatic form: [work list + request table | o_parts | lse_parts], each part
+// starting at a multiple of 256 bytes.
+struct AutoLayout {
+  int32_t kv_splits;
+  size_t list_bytes, o_off, lse_off, total;
+};
+bool auto_layout(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch,
+                 AutoLayout* lay) {
+  const int32_t s = mc_prefill_attn_suggest_kv_splits(p, prefix_lens, new_lens, batch);
+  if (s <= 0) return false;
+  int64_t total_new = 0;
+  for (int32_t r = 0; r < batch; ++r) total_new += new_lens[r];
+  lay->kv_splits = s;
+  if (s == 1) {
+    lay->list_bytes = mc_prefill_attn_workspace_bytes(p, batch, total_new);
+    lay->o_off = lay->lse_off = lay->total = lay->list_bytes;
+    return true;
+  }
+  const size_t rows = (size_t)total_new * (size_t)p->num_q_heads;
+  lay->list_bytes = mc_prefill_attn_split_workspace_bytes(p, batch, total_new, s);
+  lay->o_off = (lay->list_bytes + 255) & ~(size_t)255;
+  lay->lse_off = (lay->o_off + (size_t)s * rows * (size_t)p->head_dim * sizeof(float) + 255) & ~(size_t)255;
+  lay->total = lay->lse_off + (size_t)s * rows * sizeof(float);
+  return true;
+}
+}  // namespace
+
+size_t mc_prefill_attn_auto_workspace_bytes(const mc_attn_params* p, const int32_t* prefix_lens,
+                                            const int32_t* new_lens, int32_t batch) {
+  AutoLayout lay;
+  return auto_layout(p, prefix_lens, new_lens, batch, &lay) ? lay.total : 0;
+}
+
+mc_status mc_prefill_attn_auto(const mc_attn_params* p, const void* q, const void* k_pool, const void* v_pool,
+                               const int32_t* block_tables, int32_t max_pages_per_req,
+                               const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch, void* out,
+                               float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  AutoLayout lay;
+  if (!auto_layout(p, prefix_lens, new_lens, batch, &lay) || lay.kv_splits == 1)
+    // one slice, or arguments the whole-row call will name the fault of
+    return attn_enqueue(p, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens, batch, out, lse,
+                        0, nullptr, nullptr, workspace, workspace_bytes, hip_stream);
+  if (out == nullptr) return MC_ERR_NULL;
+  if (!aligned16(out) || (reinterpret_cast<uintptr_t>(lse) & 3u) || !aligned16(workspace)) return MC_ERR_ALIGN;
+  if (workspace == nullptr || workspace_bytes < lay.total) return MC_ERR_WORKSPACE;
+  char* ws = reinterpret_cast<char*>(workspace);
+  float* o_parts = reinterpret_cast<float*>(ws + lay.o_off);
+  float* lse_parts = reinterpret_cast<float*>(ws + lay.lse_off);
+  mc_status st = attn_enqueue(p, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens, batch,
+                              nullptr, nullptr, lay.kv_splits, o_parts, lse_parts, workspace, lay.list_bytes,
+                              hip_stream);
+  if (st != MC_OK) return st;
+  int64_t total_new = 0;
+  for (int32_t r = 0; r < batch; ++r) total_new += new_lens[r];
+  return mc_attn_merge_lse(o_parts, lse_parts, lay.kv_splits, total_new * p->num_q_heads, p->head_dim, (int32_t)p->dtype,
+                           out, lse, hip_stream);
+}
+
 mc_status mc_prefill_attn_prepare(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens,
                                   int32_t batch, int32_t kv_splits, void* workspace, size_t workspace_bytes,
                                   void* hip_stream, mc_attn_plan* plan) {

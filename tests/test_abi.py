@@ -181,3 +181,15 @@ def test_prepare_and_run_host_side(lib):
     assert prepare([8192], [8192], 0)[0] == B.MC_ERR_WORKSPACE
     assert prepare([8192], [8192], 0, FAKE, 64)[0] == B.MC_ERR_WORKSPACE
     assert prepare([8192], [8192], B.MC_MAX_KV_SPLITS + 1)[0] == B.MC_ERR_SHAPE
+
+
+def test_auto_workspace_size(lib):
+    p = good_params()
+    w = B.mc_prefill_attn_auto_workspace_bytes
+    assert w(p, [8192], [8192]) == B.mc_prefill_attn_workspace_bytes(p, 1, 8192)        # whole-row: nothing extra
+    rows, s = 16 * 64, B.mc_prefill_attn_suggest_kv_splits(p, [131056], [16])
+    need = w(p, [131056], [16])
+    lower = B.mc_prefill_attn_split_workspace_bytes(p, 1, 16, s) + s * rows * 129 * 4
+    assert s == 32 and lower <= need <= lower + 1024                                      # list + partials (+ alignment)
+    assert w(p, [-1], [16]) == 0
+    assert w(p, [], []) > 0

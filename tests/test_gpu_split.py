@@ -101,6 +101,26 @@ def test_suggested_slice_count_runs_and_matches_oracle(oracle):
     assert np.abs(lse - whole_lse).max() <= TOL[W.BF16]["lse_abs"]
 
 
+@pytest.mark.parametrize("prefix,new", [([6000], [16]), ([300, 0], [40, 700]), ([2500, 10, 0], [3, 1, 0])])
+def test_automatic_form_matches_oracle(oracle, prefix, new):
+    # the library picks whole rows or key slices + merge by itself; either way the result is the oracle's
+    pages = sum(-(-(p + c) // 16) for p, c in zip(prefix, new)) + 8
+    case = W.make_attn_case(64, W.BF16, 16, 2, 128, 16, prefix, new, pages)
+    dc = DeviceCase(case)
+    splits = B.mc_prefill_attn_suggest_kv_splits(dc.params, prefix, new)
+    need = B.mc_prefill_attn_auto_workspace_bytes(dc.params, prefix, new)
+    print(f"auto case prefix={prefix} new={new}: {splits} slices, workspace {need} B", flush=True)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    B.mc_prefill_attn_auto(dc.params, dc.q, dc.k_pool, dc.v_pool, dc.block_tables, prefix, new, dc.out, dc.lse, ws)
+    out, lse = dc.result()
+    ref_out, ref_lse, _ = oracle.case_full(case)
+    check_close(out, ref_out, W.BF16, "automatic form")
+    assert np.abs(lse - ref_lse).max() <= TOL[W.BF16]["lse_abs"]
+    with pytest.raises(B.McError):                               # one byte short of what it asks for
+        B.mc_prefill_attn_auto(dc.params, dc.q, dc.k_pool, dc.v_pool, dc.block_tables, prefix, new, dc.out, dc.lse,
+                               ws[:need - 1] if splits > 1 else ws[:8])
+
+
 def test_merge_of_foreign_partials(oracle):
     # partials that did not come from this library's kernel: -inf parts, NaN payload behind them, all-empty rows
     rng = np.random.default_rng(8)
