@@ -43,10 +43,13 @@ def measured_traffic():
 
 def mfma_ceiling():
     """Rate of back-to-back bf16 MFMAs alone on this board (zeros / ones / random operands), measured by the
-    stand-alone program built beside the library; None when it is missing or fails."""
+    stand-alone program bench_probes.hip; None when it is missing or fails."""
     import subprocess
-    exe = os.path.join(ROOT, "paper_2407_00079_amd", "mfma_ceiling")
+    exe = os.path.join(ROOT, "bench_probes")
     try:
+        if not os.path.exists(exe):
+            import __graft_entry__
+            __graft_entry__.build_bench_probes()
         out = subprocess.run([exe], capture_output=True, text=True, timeout=60, check=True).stdout.split()
         return {out[i]: {"tflops": float(out[i + 1]), "shader_mhz": float(out[i + 2])} for i in (0, 3, 6)}
     except Exception as e:      # measurement aid only: the benchmark goes on without it

@@ -4,10 +4,10 @@
  * Three operations behind Mooncake's KVCache reuse, as the paper states the
  * problem (it gives no kernel design):
  *
- *   - a prefill node gets the ids of the reusable prefix blocks and of all
- *     blocks of the request, and finishes prefill of the uncached tokens
- *     "using the prefix cache", in chunks no longer than prefill_chunk
- *     (Section 3, steps 1 and 2; Section 5.1);
+ *   - a prefill node is handed the ids of the prefix blocks it may reuse and of
+ *     all blocks of the request, loads the former and computes prefill for the
+ *     uncached tokens only, reading the reused prefix, in chunks no longer than
+ *     prefill_chunk (Section 3, steps 1 and 2; Section 5.1);
  *   - per layer, KVCache is loaded before that layer's attention and stored
  *     after it, asynchronously, overlapped with compute (Section 5.2;
  *     Section 3, step 3).
@@ -15,12 +15,24 @@
  * Conventions for every entry point:
  *   - "dev" pointers are device memory of the current HIP device, "host"
  *     pointers are ordinary host memory.  The caller owns every buffer; the
- *     library never allocates or frees device memory and never synchronises.
+ *     library never allocates or frees device memory.
  *   - All device work is enqueued on `hip_stream` (a hipStream_t passed as
  *     void*; NULL = the default stream) and the call returns at once.
  *     Host arrays are read before the call returns and may be freed then.
  *   - Arguments are validated on the host first.  On any status other than
- *     MC_OK nothing has been launched and no output has been touched.
+ *     MC_OK and MC_ERR_HIP nothing has been launched and no output has been
+ *     touched.  MC_ERR_HIP means the HIP runtime refused a step of the call:
+ *     steps of the same call that were enqueued before it (an upload, a copy,
+ *     the first of two kernels) stay enqueued, so the outputs are undefined.
+ *   - The calls that take host lengths or offsets and hand them to a kernel
+ *     (mc_prefill_attn_paged, _paged_split, _auto, _prepare, mc_kv_append_paged,
+ *     mc_prefix_hash, mc_prefix_match) upload them from a small ring of pinned
+ *     HOST slots the library owns.  Such a call may allocate a slot with
+ *     hipHostMalloc (the first calls, or a list larger than any before), and
+ *     with 256 uploads in flight it waits for the oldest: these calls are not
+ *     for stream capture.  The run calls (mc_prefill_attn_run, _run_split,
+ *     mc_kv_append_run), pack / unpack and the merge upload nothing, allocate
+ *     nothing and never wait.  Calls may come from several host threads.
  *   - Page ids that live in device memory cannot be range-checked without a
  *     sync: an id outside [0, num_pages) is undefined behaviour.
  *   - No exceptions cross this boundary.

@@ -16,7 +16,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "mc_oracle.c")
-_LIB = os.path.join(_HERE, "libmc_oracle.so")
+# MC_ORACLE_SANITIZE=1 (tests only): the same source built with AddressSanitizer and UBSan, for a
+# process that was started with the sanitizer runtime preloaded
+_SANITIZE = os.environ.get("MC_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "libmc_oracle_san.so" if _SANITIZE else "libmc_oracle.so")
 
 BF16, F32 = 0, 1
 _DTYPES = {"bf16": BF16, "f32": F32}
@@ -25,7 +28,8 @@ _DTYPES = {"bf16": BF16, "f32": F32}
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (fp64 arithmetic, no fast-math, OpenMP over rows)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+        opt = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all"] if _SANITIZE else ["-O2"]
+        cmd = ["gcc", *opt, "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
                "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB

@@ -45,14 +45,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #define MC_LDS __attribute__((address_space(3)))
 
-#ifndef MC_WAVES
-#define MC_WAVES 8
-#endif
-#ifndef MC_SKEW
-#define MC_SKEW 1
-#endif
-
-constexpr int kTileKeys = 64;          // keys per LDS tile = 4 pages of 16
+constexpr int kWaves = 8;              // waves of a workgroup: two per SIMD, 32 stacked rows each
+static_assert(kWaves * 32 == kAttnTileRows, "the host cuts the work list into tiles of kAttnTileRows rows");
+constexpr int kTileKeys = kAttnTileKeys;   // keys per LDS tile = 4 pages of 16
 constexpr int kPageTokens = 16;
 constexpr int kRowBytes = 256;         // one K or V row: 128 bf16 or 64 f32
 constexpr int kPageHeadBytes = kPageTokens * kRowBytes;   // 4 KiB, contiguous in the pool
@@ -622,7 +617,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_kernel(const AttnArgs
     // matrix pipe always has an MFMA that is ready and the vector ALU is never wanted twice.
     // Safe because phase A of a tile's first step reads nothing of the tile before it and
     // nothing of the tile after it, and every wave still passes one barrier per tile.
-    const bool late_barrier = MC_SKEW && wave_u >= WAVES / 2;
+    const bool late_barrier = wave_u >= WAVES / 2;
     // The loop body is written out for the three buffers in turn, so that inside it every tile
     // offset is a compile-time constant and goes into the LDS instructions' immediate fields.
     auto pipelined_tile = [&](auto buf_tag) __attribute__((always_inline)) {
@@ -754,17 +749,15 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
 
 }  // namespace
 
-int attn_tile_rows(int) { return MC_WAVES * 32; }
-
 hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream) {
   (void)hipGetLastError();   // drop any stale error of earlier, unrelated runtime calls
   const bool split = args.kv_splits > 0;
   if (dtype == MC_DTYPE_BF16) {
-    if (split) attn_prefill_kernel<Bf16, MC_WAVES, true><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
-    else attn_prefill_kernel<Bf16, MC_WAVES, false><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
+    if (split) attn_prefill_kernel<Bf16, kWaves, true><<<args.n_items, kWaves * 64, 0, stream>>>(args);
+    else attn_prefill_kernel<Bf16, kWaves, false><<<args.n_items, kWaves * 64, 0, stream>>>(args);
   } else {
-    if (split) attn_prefill_kernel<F32, MC_WAVES, true><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
-    else attn_prefill_kernel<F32, MC_WAVES, false><<<args.n_items, MC_WAVES * 64, 0, stream>>>(args);
+    if (split) attn_prefill_kernel<F32, kWaves, true><<<args.n_items, kWaves * 64, 0, stream>>>(args);
+    else attn_prefill_kernel<F32, kWaves, false><<<args.n_items, kWaves * 64, 0, stream>>>(args);
   }
   return hipGetLastError();
 }

@@ -20,6 +20,7 @@ namespace {
 constexpr int kThreads = 512;
 constexpr int kUnroll = 1;                        // 16-byte vectors per thread
 constexpr int kSliceVecs = kThreads * kUnroll;    // 8 KiB per workgroup
+static_assert(kSliceVecs == kKvCopySliceVecs, "the host sizes the copy grid with kKvCopySliceVecs");
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -186,8 +187,6 @@ hipError_t launch_kv_append(const void* k_new, const void* v_new, void* k_pool, 
       total_vecs, Hkv);
   return hipGetLastError();
 }
-
-int kv_copy_slice_vecs() { return kSliceVecs; }
 
 hipError_t launch_kv_copy(bool pack, const void* k_src, const void* v_src, void* k_dst, void* v_dst,
                           const int32_t* page_ids, const int32_t* order, int64_t n, int64_t page_bytes,

@@ -6,103 +6,85 @@
 #include <mutex>
 #include <vector>
 
+#include "host_plan.h"
 #include "mc_internal.h"
 
 namespace {
 
-inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-mc_status check_params(const mc_attn_params* p) {
-  if (p == nullptr) return MC_ERR_NULL;
-  if (p->num_q_heads <= 0 || p->num_kv_heads <= 0 || p->head_dim <= 0 || p->page_size <= 0 || p->num_pages <= 0)
-    return MC_ERR_SHAPE;
-  if (p->num_q_heads % p->num_kv_heads != 0) return MC_ERR_SHAPE;
-  if (p->dtype != MC_DTYPE_BF16 && p->dtype != MC_DTYPE_F32) return MC_ERR_UNSUPPORTED;
-  if (p->page_size != 16) return MC_ERR_UNSUPPORTED;
-  if (p->dtype == MC_DTYPE_BF16 && p->head_dim != 128) return MC_ERR_UNSUPPORTED;
-  if (p->dtype == MC_DTYPE_F32 && p->head_dim != 64) return MC_ERR_UNSUPPORTED;
-  if (!(p->softmax_scale >= 0.f) || std::isinf(p->softmax_scale)) return MC_ERR_SHAPE;
-  return MC_OK;
-}
-
-// upper bound on work items: per request and KV head, ceil(C_r * G / rows) <= C_r * G / rows + 1
-size_t max_items(const mc_attn_params* p, int32_t batch, int64_t total_new_tokens, int32_t kv_splits = 1) {
-  const int64_t rows = mc::attn_tile_rows(p->dtype);
-  const int64_t G = p->num_q_heads / p->num_kv_heads;
-  return (size_t)(p->num_kv_heads * ((total_new_tokens * G) / rows + batch)) * (size_t)kv_splits;
-}
+using namespace mc::host;
 
 // Pinned host slots the work list is written to before its asynchronous upload.  A slot is
 // reused only after the event recorded behind its last upload has completed, so the host copy
 // outlives the transfer.  A call never waits for the stream's earlier work: if every slot is
-// still in flight a new one is added (up to kMaxSlots; only then does a call block on the
-// oldest).  Host memory only, 64 KiB or the largest work list seen per slot, kept until the
+// still in flight a new one is added (up to SlotRing::kMaxSlots; only then does a call block on
+// the oldest).  Which slot a call gets is decided by mc::host::SlotRing under this class's lock:
+// from acquire() until in_flight() or abandon() the slot is HELD and no other thread can be
+// given it.  Host memory only, 64 KiB or the largest work list seen per slot, kept until the
 // process ends.
 class StagingRing {
  public:
-  // returns a slot with at least `bytes` of pinned memory, or nullptr if HIP refuses
+  // returns a held slot with at least `bytes` of pinned memory, or nullptr if HIP refuses
   void* acquire(size_t bytes, int* slot_out) {
     std::lock_guard<std::mutex> lock(mu_);
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return nullptr;
-    int pick = -1;
-    const int n = (int)slots_.size();
-    for (int k = 0; k < n && pick < 0; ++k) {
-      const int i = (next_ + k) % n;
-      Slot& s = slots_[i];
-      if (s.dev != dev) continue;
-      if (!s.busy || hipEventQuery(s.ev) == hipSuccess) pick = i;
-    }
-    if (pick < 0 && n < kMaxSlots) {
-      Slot s;
-      if (hipEventCreateWithFlags(&s.ev, hipEventDisableTiming) != hipSuccess) return nullptr;
-      s.dev = dev;
-      slots_.push_back(s);
-      pick = n;
-    }
-    if (pick < 0) {
-      // everything in flight and the ring is full: wait for the oldest slot of this device
-      for (int k = 0; k < n && pick < 0; ++k) {
-        const int i = (next_ + k) % n;
-        if (slots_[i].dev == dev) pick = i;
+    const SlotRing::Pick pick = ring_.pick(dev, [&](int i) { return hipEventQuery(mem_[i].ev) == hipSuccess; });
+    if (pick.slot < 0) return nullptr;
+    Mem& m = mem_[pick.slot];
+    if (pick.is_new) {
+      m = Mem{};
+      if (hipEventCreateWithFlags(&m.ev, hipEventDisableTiming) != hipSuccess) {
+        ring_.drop_new(pick.slot);
+        return nullptr;
       }
-      if (pick < 0) return nullptr;   // ring full of other devices' slots
-      if (hipEventSynchronize(slots_[pick].ev) != hipSuccess) return nullptr;
     }
-    Slot& s = slots_[pick];
-    s.busy = false;
-    if (s.cap < bytes) {
-      if (s.host != nullptr) (void)hipHostFree(s.host);
-      s.host = nullptr;
-      s.cap = 0;
+    if (pick.must_wait && hipEventSynchronize(m.ev) != hipSuccess) {
+      ring_.in_flight(pick.slot);   // still not known to be done: leave it as it was
+      return nullptr;
+    }
+    if (m.cap < bytes) {
+      if (m.host != nullptr) (void)hipHostFree(m.host);
+      m.host = nullptr;
+      m.cap = 0;
       const size_t want = std::max<size_t>(bytes, 1 << 16);
-      if (hipHostMalloc(&s.host, want, hipHostMallocDefault) != hipSuccess) return nullptr;
-      s.cap = want;
+      if (hipHostMalloc(&m.host, want, hipHostMallocDefault) != hipSuccess) {
+        m.host = nullptr;
+        ring_.abandon(pick.slot);
+        return nullptr;
+      }
+      m.cap = want;
     }
-    *slot_out = pick;
-    next_ = (pick + 1) % (int)slots_.size();
-    return s.host;
+    *slot_out = pick.slot;
+    return m.host;
   }
+  // the upload from the slot has been enqueued on `stream`: the slot is free again once the
+  // stream has passed this point.  If the event cannot be recorded the stream is waited for
+  // instead, so the slot never returns to the ring while a copy may still read it.
   bool release_after(int slot, hipStream_t stream) {
     std::lock_guard<std::mutex> lock(mu_);
-    Slot& s = slots_[slot];
-    if (hipEventRecord(s.ev, stream) != hipSuccess) return false;
-    s.busy = true;
-    return true;
+    if (hipEventRecord(mem_[slot].ev, stream) == hipSuccess) {
+      ring_.in_flight(slot);
+      return true;
+    }
+    (void)hipStreamSynchronize(stream);
+    ring_.abandon(slot);
+    return false;
+  }
+  // nothing was enqueued from the slot
+  void abandon(int slot) {
+    std::lock_guard<std::mutex> lock(mu_);
+    ring_.abandon(slot);
   }
 
  private:
-  static constexpr int kMaxSlots = 256;
-  struct Slot {
+  struct Mem {
     void* host = nullptr;
     size_t cap = 0;
     hipEvent_t ev = nullptr;
-    int dev = -1;
-    bool busy = false;
   };
   std::mutex mu_;
-  std::vector<Slot> slots_;
-  int next_ = 0;
+  SlotRing ring_;
+  Mem mem_[SlotRing::kMaxSlots];
 };
 
 StagingRing g_staging;
@@ -127,108 +109,12 @@ const char* mc_status_string(mc_status s) {
 
 size_t mc_prefill_attn_workspace_bytes(const mc_attn_params* p, int32_t batch, int64_t total_new_tokens) {
   if (check_params(p) != MC_OK || batch < 0 || total_new_tokens < 0) return 0;
-  return sizeof(mc::AttnItem) * max_items(p, batch, total_new_tokens) + sizeof(mc::AttnReq) * (size_t)batch + 64;
+  return list_bytes(p, batch, total_new_tokens);
 }
 
 }  // extern "C"
 
 namespace {
-
-// Work list of an attention launch: one item per (request, KV head, tile of stacked rows) and, for
-// split launches (kv_splits >= 1), per key slice - most keys first, dealt round-robin so that
-// consecutive workgroup ids (which land on different XCDs) take different (request, KV head)
-// streams and each XCD's L2 keeps one stream hot.  Lengths have been validated by the caller.
-void build_work_list(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch,
-                     int32_t kv_splits, std::vector<mc::AttnReq>& reqs, std::vector<mc::AttnItem>& items) {
-  const bool split = kv_splits > 0;
-  const int G = p->num_q_heads / p->num_kv_heads;
-  const int rows = mc::attn_tile_rows(p->dtype);
-  reqs.assign((size_t)batch, mc::AttnReq{});
-  struct Keyed {
-    int64_t cost;
-    mc::AttnItem it;
-  };
-  constexpr int kXcd = 8;
-  std::vector<Keyed> lanes[kXcd];
-  int64_t q_off = 0;
-  for (int32_t r = 0; r < batch; ++r) {
-    const int32_t P = prefix_lens[r], C = new_lens[r];
-    reqs[(size_t)r] = {(int32_t)q_off, P, C, (int32_t)(((int64_t)P + C + p->page_size - 1) / p->page_size)};
-    q_off += C;
-    const int64_t n_rows = (int64_t)C * G;
-    for (int32_t g = 0; g < p->num_kv_heads; ++g)
-      for (int64_t row0 = 0; row0 < n_rows; row0 += rows) {
-        const int64_t tok_last = std::min<int64_t>(C - 1, (row0 + rows - 1) / G);
-        const int64_t keys = P + tok_last + 1;                 // keys the tile's last row sees
-        if (!split) {
-          lanes[(r * p->num_kv_heads + g) % kXcd].push_back({keys, {r, g, (int32_t)row0, 0}});
-          continue;
-        }
-        // slices of whole 64-key tiles, ceil(tiles of the request / kv_splits) each; every slice gets
-        // an item, also one past what the tile can see (it writes zeros and -inf)
-        const int64_t per = ((((int64_t)P + C + 63) / 64) + kv_splits - 1) / kv_splits * 64;
-        for (int32_t sl = 0; sl < kv_splits; ++sl) {
-          const int64_t cost = std::max<int64_t>(0, std::min<int64_t>(keys, (sl + 1) * per) - sl * per);
-          lanes[(r * p->num_kv_heads + g + sl) % kXcd].push_back({cost, {r, g, (int32_t)row0, sl}});
-        }
-      }
-  }
-  size_t n_items = 0;
-  for (auto& l : lanes) {
-    std::stable_sort(l.begin(), l.end(), [](const Keyed& a, const Keyed& b) { return a.cost > b.cost; });
-    n_items += l.size();
-  }
-  items.clear();
-  items.reserve(n_items);
-  size_t cur[kXcd] = {0};
-  int x = 0;
-  while (items.size() < n_items) {
-    // next non-empty lane, starting from the one whose turn it is
-    int tries = 0;
-    while (cur[x] >= lanes[x].size() && tries < kXcd) {
-      x = (x + 1) % kXcd;
-      ++tries;
-    }
-    items.push_back(lanes[x][cur[x]++].it);
-    x = (x + 1) % kXcd;
-  }
-}
-
-// Lengths of a batch: sign and range checks, sum of the new tokens, most pages any request
-// with new tokens needs.
-mc_status check_lens(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch,
-                     int64_t* total_new, int32_t* need_pages) {
-  *total_new = 0;
-  *need_pages = 0;
-  for (int32_t r = 0; r < batch; ++r) {
-    if (prefix_lens[r] < 0 || new_lens[r] < 0) return MC_ERR_SHAPE;
-    const int64_t len = (int64_t)prefix_lens[r] + new_lens[r];
-    if (len > INT32_MAX - 1024) return MC_ERR_RANGE;
-    if (new_lens[r] > 0) {
-      const int32_t pages = (int32_t)((len + p->page_size - 1) / p->page_size);
-      *need_pages = pages > *need_pages ? pages : *need_pages;
-    }
-    *total_new += new_lens[r];
-  }
-  return MC_OK;
-}
-
-// Everything an attention launch checks besides the lengths.  kv_splits == 0: the whole-row kernel
-// writes out / lse.  kv_splits >= 1: the split kernel writes partials (out / lse unused).
-mc_status check_attn_buffers(bool split, const void* q, const void* k_pool, const void* v_pool,
-                             const int32_t* block_tables, int32_t batch, int32_t max_pages_per_req, int32_t need_pages,
-                             const void* out, const float* lse, const float* o_parts, const float* lse_parts,
-                             const void* workspace) {
-  if (max_pages_per_req < need_pages) return MC_ERR_SHAPE;
-  if (q == nullptr || k_pool == nullptr || v_pool == nullptr || block_tables == nullptr) return MC_ERR_NULL;
-  if (split ? (o_parts == nullptr || lse_parts == nullptr) : out == nullptr) return MC_ERR_NULL;
-  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(out) || !aligned16(workspace) ||
-      !aligned16(o_parts) || (reinterpret_cast<uintptr_t>(block_tables) & 3u) ||
-      (reinterpret_cast<uintptr_t>(lse) & 3u) || (reinterpret_cast<uintptr_t>(lse_parts) & 3u))
-    return MC_ERR_ALIGN;
-  if ((int64_t)batch * max_pages_per_req > INT32_MAX) return MC_ERR_RANGE;
-  return MC_OK;
-}
 
 // Build the work list and the request table of a batch and enqueue their upload into the
 // workspace; fill `plan` with what a later launch needs to know on the host.  The lengths have
@@ -237,11 +123,9 @@ mc_status prepare_attn(const mc_attn_params* p, const int32_t* prefix_lens, cons
                        int32_t kv_splits, int64_t total_new, int32_t need_pages, void* workspace,
                        size_t workspace_bytes, hipStream_t stream, mc_attn_plan* plan) {
   const bool split = kv_splits > 0;
-  if (total_new * p->num_q_heads > INT32_MAX) return MC_ERR_RANGE;
-  const size_t n_max = max_items(p, batch, total_new, split ? kv_splits : 1);
-  if (n_max > (size_t)INT32_MAX) return MC_ERR_RANGE;
-  if (workspace == nullptr ||
-      workspace_bytes < sizeof(mc::AttnItem) * n_max + sizeof(mc::AttnReq) * (size_t)batch + 64)
+  const mc_status range = check_list_range(p, batch, total_new, kv_splits);
+  if (range != MC_OK) return range;
+  if (workspace == nullptr || workspace_bytes < list_bytes(p, batch, total_new, split ? kv_splits : 1))
     return MC_ERR_WORKSPACE;
   if (!aligned16(workspace)) return MC_ERR_ALIGN;
 
@@ -259,7 +143,10 @@ mc_status prepare_attn(const mc_attn_params* p, const int32_t* prefix_lens, cons
   if (host == nullptr) return MC_ERR_HIP;
   std::memcpy(host, items.data(), items_bytes);
   std::memcpy(host + reqs_off, reqs.data(), sizeof(mc::AttnReq) * reqs.size());
-  if (hipMemcpyAsync(workspace, host, up_bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
+  if (hipMemcpyAsync(workspace, host, up_bytes, hipMemcpyHostToDevice, stream) != hipSuccess) {
+    g_staging.abandon(slot);
+    return MC_ERR_HIP;
+  }
   if (!g_staging.release_after(slot, stream)) return MC_ERR_HIP;
 
   plan->n_items = (int32_t)n_items;
@@ -332,17 +219,6 @@ mc_status attn_enqueue(const mc_attn_params* p, const void* q, const void* k_poo
                              lse_parts, workspace, stream);
 }
 
-// A plan handed back by the caller: made for these params, of the wanted form, not empty.
-mc_status check_plan(const mc_attn_params* p, const mc_attn_plan* plan, bool want_split) {
-  if (plan == nullptr) return MC_ERR_NULL;
-  if (plan->num_q_heads != p->num_q_heads || plan->num_kv_heads != p->num_kv_heads || plan->dtype != (int32_t)p->dtype ||
-      plan->n_items < 0 || plan->batch < 0 || plan->total_new_tokens < 0 || plan->reqs_offset < 0 ||
-      (plan->reqs_offset & 15) != 0 || plan->kv_splits < 0 || plan->kv_splits > MC_MAX_KV_SPLITS)
-    return MC_ERR_SHAPE;
-  if (want_split != (plan->kv_splits > 0)) return MC_ERR_SHAPE;
-  return MC_OK;
-}
-
 }  // namespace
 
 extern "C" {
@@ -359,8 +235,7 @@ size_t mc_prefill_attn_split_workspace_bytes(const mc_attn_params* p, int32_t ba
                                              int32_t kv_splits) {
   if (check_params(p) != MC_OK || batch < 0 || total_new_tokens < 0 || kv_splits < 1 || kv_splits > MC_MAX_KV_SPLITS)
     return 0;
-  return sizeof(mc::AttnItem) * max_items(p, batch, total_new_tokens, kv_splits) +
-         sizeof(mc::AttnReq) * (size_t)batch + 64;
+  return list_bytes(p, batch, total_new_tokens, kv_splits);
 }
 
 mc_status mc_prefill_attn_paged_split(const mc_attn_params* p, const void* q, const void* k_pool,
@@ -372,34 +247,6 @@ mc_status mc_prefill_attn_paged_split(const mc_attn_params* p, const void* q, co
   return attn_enqueue(p, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens, batch, nullptr,
                       nullptr, kv_splits, o_parts, lse_parts, workspace, workspace_bytes, hip_stream);
 }
-
-namespace {
-// Workspace of the automatic form: [work list + request table | o_parts | lse_parts], each part
-// starting at a multiple of 256 bytes.
-struct AutoLayout {
-  int32_t kv_splits;
-  size_t list_bytes, o_off, lse_off, total;
-};
-bool auto_layout(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch,
-                 AutoLayout* lay) {
-  const int32_t s = mc_prefill_attn_suggest_kv_splits(p, prefix_lens, new_lens, batch);
-  if (s <= 0) return false;
-  int64_t total_new = 0;
-  for (int32_t r = 0; r < batch; ++r) total_new += new_lens[r];
-  lay->kv_splits = s;
-  if (s == 1) {
-    lay->list_bytes = mc_prefill_attn_workspace_bytes(p, batch, total_new);
-    lay->o_off = lay->lse_off = lay->total = lay->list_bytes;
-    return true;
-  }
-  const size_t rows = (size_t)total_new * (size_t)p->num_q_heads;
-  lay->list_bytes = mc_prefill_attn_split_workspace_bytes(p, batch, total_new, s);
-  lay->o_off = (lay->list_bytes + 255) & ~(size_t)255;
-  lay->lse_off = (lay->o_off + (size_t)s * rows * (size_t)p->head_dim * sizeof(float) + 255) & ~(size_t)255;
-  lay->total = lay->lse_off + (size_t)s * rows * sizeof(float);
-  return true;
-}
-}  // namespace
 
 size_t mc_prefill_attn_auto_workspace_bytes(const mc_attn_params* p, const int32_t* prefix_lens,
                                             const int32_t* new_lens, int32_t batch) {
@@ -417,7 +264,7 @@ mc_status mc_prefill_attn_auto(const mc_attn_params* p, const void* q, const voi
     return attn_enqueue(p, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens, batch, out, lse,
                         0, nullptr, nullptr, workspace, workspace_bytes, hip_stream);
   if (out == nullptr) return MC_ERR_NULL;
-  if (!aligned16(out) || (reinterpret_cast<uintptr_t>(lse) & 3u) || !aligned16(workspace)) return MC_ERR_ALIGN;
+  if (!aligned16(out) || !aligned4(lse) || !aligned16(workspace)) return MC_ERR_ALIGN;
   if (workspace == nullptr || workspace_bytes < lay.total) return MC_ERR_WORKSPACE;
   char* ws = reinterpret_cast<char*>(workspace);
   float* o_parts = reinterpret_cast<float*>(ws + lay.o_off);
@@ -501,7 +348,7 @@ mc_status mc_kv_append_run(const mc_attn_params* p, const mc_attn_plan* plan, co
   if (k_new == nullptr || v_new == nullptr || k_pool == nullptr || v_pool == nullptr || block_tables == nullptr)
     return MC_ERR_NULL;
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(workspace) ||
-      (reinterpret_cast<uintptr_t>(block_tables) & 3u))
+      !aligned4(block_tables))
     return MC_ERR_ALIGN;
   const int64_t total_new = plan->total_new_tokens;
   if (total_new > INT32_MAX || total_new * p->num_kv_heads * 16 / 256 + 1 > INT32_MAX ||
@@ -519,64 +366,12 @@ mc_status mc_kv_append_run(const mc_attn_params* p, const mc_attn_plan* plan, co
 mc_status mc_prefill_attn_plan(const mc_attn_params* p, const int32_t* prefix_lens, const int32_t* new_lens,
                                int32_t batch, int32_t kv_splits, int32_t* items, int64_t capacity,
                                int64_t* n_items) {
-  mc_status st = check_params(p);
-  if (st != MC_OK) return st;
-  if (batch < 0 || kv_splits < 0 || kv_splits > MC_MAX_KV_SPLITS || capacity < 0) return MC_ERR_SHAPE;
-  if (n_items == nullptr || (batch > 0 && (prefix_lens == nullptr || new_lens == nullptr))) return MC_ERR_NULL;
-  if (capacity > 0 && items == nullptr) return MC_ERR_NULL;
-  int64_t total_new = 0;
-  for (int32_t r = 0; r < batch; ++r) {
-    if (prefix_lens[r] < 0 || new_lens[r] < 0) return MC_ERR_SHAPE;
-    if ((int64_t)prefix_lens[r] + new_lens[r] > INT32_MAX - 1024) return MC_ERR_RANGE;
-    total_new += new_lens[r];
-  }
-  if (total_new * p->num_q_heads > INT32_MAX) return MC_ERR_RANGE;
-  if (max_items(p, batch, total_new, kv_splits > 0 ? kv_splits : 1) > (size_t)INT32_MAX) return MC_ERR_RANGE;
-  std::vector<mc::AttnReq> reqs;
-  std::vector<mc::AttnItem> list;
-  build_work_list(p, prefix_lens, new_lens, batch, kv_splits, reqs, list);
-  *n_items = (int64_t)list.size();
-  if ((int64_t)list.size() > capacity) return capacity == 0 && items == nullptr ? MC_OK : MC_ERR_WORKSPACE;
-  static_assert(sizeof(mc::AttnItem) == 4 * sizeof(int32_t), "an item is four int32");
-  if (!list.empty()) std::memcpy(items, list.data(), sizeof(mc::AttnItem) * list.size());
-  return MC_OK;
+  return plan_items(p, prefix_lens, new_lens, batch, kv_splits, items, capacity, n_items);
 }
 
 int32_t mc_prefill_attn_suggest_kv_splits(const mc_attn_params* p, const int32_t* prefix_lens,
                                           const int32_t* new_lens, int32_t batch) {
-  if (check_params(p) != MC_OK || batch < 0) return 0;
-  if (batch > 0 && (prefix_lens == nullptr || new_lens == nullptr)) return 0;
-  constexpr int64_t kComputeUnits = 256;   // MI355X
-  constexpr int64_t kMinTilesPerSlice = 8;
-  const int64_t tile_rows = mc::attn_tile_rows(p->dtype);
-  const int64_t G = p->num_q_heads / p->num_kv_heads;
-  int64_t items = 0, most_tiles = 0;
-  for (int32_t r = 0; r < batch; ++r) {
-    if (prefix_lens[r] < 0 || new_lens[r] < 0) return 0;
-    if (new_lens[r] == 0) continue;
-    items += (int64_t)p->num_kv_heads * (((int64_t)new_lens[r] * G + tile_rows - 1) / tile_rows);
-    const int64_t tiles = ((int64_t)prefix_lens[r] + new_lens[r] + 63) / 64;
-    most_tiles = tiles > most_tiles ? tiles : most_tiles;
-  }
-  // Work items of about equal length run in rounds of one per compute unit: s slices turn `items`
-  // items into items * s of 1/s the length, ceil(items * s / 256) / s rounds of the original
-  // length, and each extra slice costs about 1 % in partial results written and merged
-  // (measured at 128k context).  The cheapest count wins, the smaller one on a tie.  From four
-  // full rounds on, the launch order (longest items first) already balances the tail.
-  if (items == 0 || items >= 4 * kComputeUnits) return 1;
-  int64_t most = most_tiles / kMinTilesPerSlice;
-  most = most < MC_MAX_KV_SPLITS ? most : MC_MAX_KV_SPLITS;
-  int32_t best = 1;
-  double best_cost = 0.0;
-  for (int64_t sl = 1; sl <= most || sl == 1; ++sl) {
-    const double rounds = (double)((items * sl + kComputeUnits - 1) / kComputeUnits) / (double)sl;
-    const double cost = rounds * (1.0 + 0.01 * (double)(sl - 1));
-    if (sl == 1 || cost < best_cost) {
-      best = (int32_t)sl;
-      best_cost = cost;
-    }
-  }
-  return best;
+  return suggest_kv_splits(p, prefix_lens, new_lens, batch);
 }
 
 mc_status mc_attn_merge_lse(const float* o_parts, const float* lse_parts, int32_t kv_splits, int64_t rows,
@@ -586,8 +381,8 @@ mc_status mc_attn_merge_lse(const float* o_parts, const float* lse_parts, int32_
     return MC_ERR_UNSUPPORTED;
   if (rows == 0) return MC_OK;
   if (o_parts == nullptr || lse_parts == nullptr || out == nullptr) return MC_ERR_NULL;
-  if (!aligned16(o_parts) || !aligned16(out) || (reinterpret_cast<uintptr_t>(lse_parts) & 3u) ||
-      (reinterpret_cast<uintptr_t>(lse) & 3u))
+  if (!aligned16(o_parts) || !aligned16(out) || !aligned4(lse_parts) ||
+      !aligned4(lse))
     return MC_ERR_ALIGN;
   if (rows > INT32_MAX) return MC_ERR_RANGE;
   if (mc::launch_attn_merge(dtype, o_parts, lse_parts, kv_splits, rows, out, lse,
@@ -621,7 +416,7 @@ mc_status mc_kv_append_paged(const mc_attn_params* p, const void* k_new, const v
   if (k_new == nullptr || v_new == nullptr || k_pool == nullptr || v_pool == nullptr || block_tables == nullptr)
     return MC_ERR_NULL;
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(workspace) ||
-      (reinterpret_cast<uintptr_t>(block_tables) & 3u))
+      !aligned4(block_tables))
     return MC_ERR_ALIGN;
   if (total_new > INT32_MAX || total_new * p->num_kv_heads * 16 / 256 + 1 > INT32_MAX ||
       (int64_t)batch * max_pages_per_req > INT32_MAX)
@@ -639,7 +434,10 @@ mc_status mc_kv_append_paged(const mc_attn_params* p, const void* k_new, const v
                (int32_t)(((int64_t)prefix_lens[r] + new_lens[r] + p->page_size - 1) / p->page_size)};
     q_off += new_lens[r];
   }
-  if (hipMemcpyAsync(workspace, host, up_bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
+  if (hipMemcpyAsync(workspace, host, up_bytes, hipMemcpyHostToDevice, stream) != hipSuccess) {
+    g_staging.abandon(slot);
+    return MC_ERR_HIP;
+  }
   if (!g_staging.release_after(slot, stream)) return MC_ERR_HIP;
   if (mc::launch_kv_append(k_new, v_new, k_pool, v_pool, block_tables, max_pages_per_req,
                            reinterpret_cast<const mc::AttnReq*>(workspace), batch, total_new, p->num_kv_heads,
@@ -648,25 +446,11 @@ mc_status mc_kv_append_paged(const mc_attn_params* p, const void* k_new, const v
   return MC_OK;
 }
 
-static mc_status check_copy(const void* a, const void* b, int64_t num_pages, int64_t page_bytes, const int32_t* ids,
-                            int64_t n, const void* c, const void* d) {
-  if (num_pages < 0 || page_bytes < 0 || n < 0) return MC_ERR_SHAPE;
-  if (page_bytes % 16 != 0) return MC_ERR_ALIGN;
-  if (n == 0 || page_bytes == 0) return MC_OK;
-  if (a == nullptr || b == nullptr || c == nullptr || d == nullptr || ids == nullptr) return MC_ERR_NULL;
-  if (num_pages == 0) return MC_ERR_SHAPE;
-  if (!aligned16(a) || !aligned16(b) || !aligned16(c) || !aligned16(d) || (reinterpret_cast<uintptr_t>(ids) & 3u))
-    return MC_ERR_ALIGN;
-  const int64_t slices = (page_bytes / 16 + mc::kv_copy_slice_vecs() - 1) / mc::kv_copy_slice_vecs();
-  if (n > INT32_MAX || n * slices > INT32_MAX) return MC_ERR_RANGE;
-  return MC_OK;
-}
-
 mc_status mc_kv_page_order(const int32_t* page_ids, int64_t n, int32_t* order, void* hip_stream) {
   if (n < 0) return MC_ERR_SHAPE;
   if (n == 0) return MC_OK;
   if (page_ids == nullptr || order == nullptr) return MC_ERR_NULL;
-  if ((reinterpret_cast<uintptr_t>(page_ids) & 3u) || (reinterpret_cast<uintptr_t>(order) & 3u)) return MC_ERR_ALIGN;
+  if (!aligned4(page_ids) || !aligned4(order)) return MC_ERR_ALIGN;
   if (n > (int64_t)1 << 20) return MC_ERR_RANGE;   // quadratic in n: a request's page list, not a pool
   if (mc::launch_kv_page_order(page_ids, n, order, reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return MC_ERR_HIP;
@@ -678,7 +462,7 @@ mc_status mc_kv_check_page_ids(const int32_t* page_ids, int64_t n, int64_t num_p
   if (n < 0 || num_pages < 0) return MC_ERR_SHAPE;
   if (n == 0) return MC_OK;
   if (page_ids == nullptr || report == nullptr) return MC_ERR_NULL;
-  if ((reinterpret_cast<uintptr_t>(page_ids) & 3u) || (reinterpret_cast<uintptr_t>(report) & 3u)) return MC_ERR_ALIGN;
+  if (!aligned4(page_ids) || !aligned4(report)) return MC_ERR_ALIGN;
   if (n > INT32_MAX) return MC_ERR_RANGE;
   if (mc::launch_kv_check_page_ids(page_ids, n, num_pages, report, reinterpret_cast<hipStream_t>(hip_stream)) !=
       hipSuccess)
@@ -691,7 +475,7 @@ mc_status mc_kv_pack_layer_ordered(const void* k_pool_layer, const void* v_pool_
                                    void* k_out, void* v_out, void* hip_stream) {
   mc_status st = check_copy(k_pool_layer, v_pool_layer, num_pages, page_bytes, page_ids, n, k_out, v_out);
   if (st != MC_OK || n == 0 || page_bytes == 0) return st;
-  if (reinterpret_cast<uintptr_t>(order) & 3u) return MC_ERR_ALIGN;
+  if (!aligned4(order)) return MC_ERR_ALIGN;
   if (mc::launch_kv_copy(true, k_pool_layer, v_pool_layer, k_out, v_out, page_ids, order, n, page_bytes,
                          reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return MC_ERR_HIP;
@@ -703,7 +487,7 @@ mc_status mc_kv_unpack_layer_ordered(const void* k_in, const void* v_in, int64_t
                                      void* v_pool_layer, void* hip_stream) {
   mc_status st = check_copy(k_in, v_in, num_pages, page_bytes, page_ids, n, k_pool_layer, v_pool_layer);
   if (st != MC_OK || n == 0 || page_bytes == 0) return st;
-  if (reinterpret_cast<uintptr_t>(order) & 3u) return MC_ERR_ALIGN;
+  if (!aligned4(order)) return MC_ERR_ALIGN;
   if (mc::launch_kv_copy(false, k_in, v_in, k_pool_layer, v_pool_layer, page_ids, order, n, page_bytes,
                          reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return MC_ERR_HIP;
@@ -781,8 +565,8 @@ mc_status mc_prefix_hash(const int32_t* tokens, const int64_t* tok_offsets, int3
   const int64_t total_blocks = key_off[batch];
   if (total_blocks == 0) return MC_OK;
   if (tokens == nullptr || keys == nullptr) return MC_ERR_NULL;
-  if ((reinterpret_cast<uintptr_t>(tokens) & 3u) || (reinterpret_cast<uintptr_t>(keys) & 7u) ||
-      (reinterpret_cast<uintptr_t>(workspace) & 15u))
+  if (!aligned4(tokens) || (reinterpret_cast<uintptr_t>(keys) & 7u) ||
+      !aligned16(workspace))
     return MC_ERR_ALIGN;
   if (max_blocks > (1 << 26) - 8) return MC_ERR_RANGE;   // four blocks per workgroup along grid x
   if (workspace == nullptr || workspace_bytes < mc_prefix_hash_workspace_bytes(batch)) return MC_ERR_WORKSPACE;
@@ -793,7 +577,10 @@ mc_status mc_prefix_hash(const int32_t* tokens, const int64_t* tok_offsets, int3
   void* host = g_staging.acquire(up, &slot);
   if (host == nullptr) return MC_ERR_HIP;
   std::memcpy(host, tab.data(), up);
-  if (hipMemcpyAsync(workspace, host, up, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
+  if (hipMemcpyAsync(workspace, host, up, hipMemcpyHostToDevice, stream) != hipSuccess) {
+    g_staging.abandon(slot);
+    return MC_ERR_HIP;
+  }
   if (!g_staging.release_after(slot, stream)) return MC_ERR_HIP;
   const int64_t* dev_tab = reinterpret_cast<const int64_t*>(workspace);
   if (mc::launch_prefix_hash(tokens, dev_tab, dev_tab + batch + 1, batch, block_tokens, max_blocks, keys, stream) !=
@@ -824,8 +611,8 @@ mc_status mc_prefix_match(const uint64_t* keys, const int64_t* key_offsets, int3
       (cache_offsets[n_inst] > cache_offsets[0] && cache_keys == nullptr))
     return MC_ERR_NULL;
   if ((reinterpret_cast<uintptr_t>(keys) & 7u) || (reinterpret_cast<uintptr_t>(cache_keys) & 7u) ||
-      (reinterpret_cast<uintptr_t>(prefix_len) & 3u) || (reinterpret_cast<uintptr_t>(best_len) & 3u) ||
-      (reinterpret_cast<uintptr_t>(best_inst) & 3u) || (reinterpret_cast<uintptr_t>(workspace) & 15u))
+      !aligned4(prefix_len) || !aligned4(best_len) ||
+      !aligned4(best_inst) || !aligned16(workspace))
     return MC_ERR_ALIGN;
   if (batch > 65535) return MC_ERR_RANGE;   // the match grid's second dimension
   if (workspace == nullptr || workspace_bytes < mc_prefix_match_workspace_bytes(batch, n_inst)) return MC_ERR_WORKSPACE;
@@ -837,7 +624,10 @@ mc_status mc_prefix_match(const uint64_t* keys, const int64_t* key_offsets, int3
   if (host == nullptr) return MC_ERR_HIP;
   std::memcpy(host, key_offsets, sizeof(int64_t) * ((size_t)batch + 1));
   std::memcpy(host + batch + 1, cache_offsets, sizeof(int64_t) * ((size_t)n_inst + 1));
-  if (hipMemcpyAsync(workspace, host, up, hipMemcpyHostToDevice, stream) != hipSuccess) return MC_ERR_HIP;
+  if (hipMemcpyAsync(workspace, host, up, hipMemcpyHostToDevice, stream) != hipSuccess) {
+    g_staging.abandon(slot);
+    return MC_ERR_HIP;
+  }
   if (!g_staging.release_after(slot, stream)) return MC_ERR_HIP;
   const int64_t* dev_tab = reinterpret_cast<const int64_t*>(workspace);
   if (mc::launch_prefix_match(keys, dev_tab, batch, cache_keys, dev_tab + batch + 1, n_inst, prefix_len, best_len,

@@ -4,25 +4,9 @@
 #include <stdint.h>
 
 #include "mc.h"
+#include "mc_types.h"
 
 namespace mc {
-
-// One unit of attention work: a tile of stacked query rows of one (request, KV head).
-// Stacked row index = token_in_chunk * G + head_in_group, so one K/V tile in LDS
-// feeds all G query heads of the group.
-struct AttnItem {
-  int32_t req;
-  int32_t kv_head;
-  int32_t row0;   // first stacked row of the tile
-  int32_t slice;  // key slice of the request this item covers (split launches only, else 0)
-};
-
-struct AttnReq {
-  int32_t q_off;   // index of the request's first new token in q / out
-  int32_t prefix;  // P_r
-  int32_t chunk;   // C_r
-  int32_t pages;   // ceil((P_r + C_r) / S): entries of the block-table row that may be read
-};
 
 struct AttnArgs {
   const void* q;
@@ -44,18 +28,12 @@ struct AttnArgs {
   float* lse_parts;
 };
 
-// rows of stacked queries one workgroup covers, per dtype (host needs it to cut the work list)
-int attn_tile_rows(int dtype);
-
 // enqueue the attention kernel over args.n_items work items
 hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream);
 
 // enqueue the merge of kv_splits partial results over `rows` rows into out (dtype) and lse (or null)
 hipError_t launch_attn_merge(int dtype, const float* o_parts, const float* lse_parts, int kv_splits, int64_t rows,
                              void* out, float* lse, hipStream_t stream);
-
-// 16-byte vectors of a page one copy workgroup moves (host needs it for the grid-size range check)
-int kv_copy_slice_vecs();
 
 // enqueue gather (pack) or scatter (unpack) of n pages of page_bytes for K and V; `order` (or null)
 // lists the positions of page_ids in the order the workgroups should take them
