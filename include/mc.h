@@ -183,6 +183,30 @@ mc_status mc_prefill_attn_auto(const mc_attn_params* p, const void* q, const voi
                                float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * mc_prefill_attn_paged for callers that cannot allocate: code under HIP graph capture, serving
+ * loops and harnesses that forbid hipMalloc.  Same arguments without the workspace, same result
+ * (the same kernel over the same work list).  The work list and request table live in a fixed
+ * device array inside the library (MC_NOALLOC_MAX_ITEMS * 16 + MC_NOALLOC_MAX_BATCH * 16 bytes
+ * = 514 KiB per GPU, held until the process ends) and are built ON the device by a small kernel
+ * that receives the lengths as a kernel argument: the call allocates nothing (device, pinned or
+ * host heap), uploads nothing and never waits; it enqueues two kernels on `hip_stream`.
+ *
+ * Limits: batch <= MC_NOALLOC_MAX_BATCH and at most MC_NOALLOC_MAX_ITEMS work items
+ * (sum over requests of Hkv * ceil(C_r * Hq / Hkv / 256)); beyond them the call returns
+ * MC_ERR_RANGE and enqueues nothing.  Every call on a GPU uses that GPU's one array: calls whose
+ * device work may overlap (different streams without an ordering between them) race on it; calls
+ * on one stream, or ordered by events, are safe.  The first call on a device looks the array's
+ * address up (hipGetSymbolAddress) and should be made outside stream capture.
+ */
+#define MC_NOALLOC_MAX_BATCH 128
+#define MC_NOALLOC_MAX_ITEMS 32768
+mc_status mc_prefill_attn_paged_noalloc(const mc_attn_params* p, const void* q, const void* k_pool,
+                                        const void* v_pool, const int32_t* block_tables,
+                                        int32_t max_pages_per_req, const int32_t* prefix_lens,
+                                        const int32_t* new_lens, int32_t batch, void* out, float* lse,
+                                        void* hip_stream);
+
+/*
  * Prepare once, run per layer.  The work list and the request table depend on the lengths of the
  * batch only, and a prefill pass makes the same attention and append calls for every layer of
  * the model (Section 5.2: layer-wise prefill): mc_prefill_attn_prepare builds them and enqueues

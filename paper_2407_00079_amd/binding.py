@@ -25,7 +25,8 @@ EXPORTS = ("mc_status_string", "mc_prefill_attn_workspace_bytes", "mc_prefill_at
            "mc_prefix_match_workspace_bytes", "mc_prefix_match", "mc_kv_page_order", "mc_kv_pack_layer_ordered",
            "mc_kv_unpack_layer_ordered", "mc_prefill_attn_suggest_kv_splits", "mc_kv_check_page_ids",
            "mc_prefill_attn_plan", "mc_prefill_attn_prepare", "mc_prefill_attn_run", "mc_prefill_attn_run_split",
-           "mc_kv_append_run", "mc_prefill_attn_auto_workspace_bytes", "mc_prefill_attn_auto")
+           "mc_kv_append_run", "mc_prefill_attn_auto_workspace_bytes", "mc_prefill_attn_auto",
+           "mc_prefill_attn_paged_noalloc")
 MC_MAX_KV_SPLITS = 256
 
 
@@ -93,6 +94,8 @@ def lib():
         l.mc_prefill_attn_auto_workspace_bytes.argtypes = [pp, vp, vp, i32]
         l.mc_prefill_attn_auto.restype = ctypes.c_int
         l.mc_prefill_attn_auto.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp]
+        l.mc_prefill_attn_paged_noalloc.restype = ctypes.c_int
+        l.mc_prefill_attn_paged_noalloc.argtypes = [pp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp, vp]
         l.mc_prefill_attn_prepare.restype = ctypes.c_int
         l.mc_prefill_attn_prepare.argtypes = [pp, vp, vp, i32, i32, vp, ctypes.c_size_t, vp, pl_]
         l.mc_prefill_attn_run.restype = ctypes.c_int
@@ -202,6 +205,25 @@ def mc_prefill_attn_auto(params: McAttnParams, q, k_pool, v_pool, block_tables, 
                                         _dev_ptr(workspace), ws_bytes, _stream_handle(stream)))
     if st != MC_OK:
         raise McError(st, "mc_prefill_attn_auto")
+
+
+def mc_prefill_attn_paged_noalloc_raw(params, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens,
+                                      new_lens, batch, out, lse, hip_stream) -> int:
+    return int(lib().mc_prefill_attn_paged_noalloc(ctypes.byref(params) if params is not None else None, q, k_pool,
+                                                   v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens,
+                                                   batch, out, lse, hip_stream))
+
+
+def mc_prefill_attn_paged_noalloc(params: McAttnParams, q, k_pool, v_pool, block_tables, prefix_lens, new_lens, out,
+                                  lse=None, stream=None) -> None:
+    """mc_prefill_attn_paged without a workspace: the work list is built on the device in the library's own
+    fixed array (no allocation, no upload)."""
+    batch, pl, nl = _lens(prefix_lens, new_lens)
+    st = mc_prefill_attn_paged_noalloc_raw(params, _dev_ptr(q), _dev_ptr(k_pool), _dev_ptr(v_pool),
+                                           _dev_ptr(block_tables), _max_pages(block_tables), pl, nl, batch,
+                                           _dev_ptr(out), _dev_ptr(lse), _stream_handle(stream))
+    if st != MC_OK:
+        raise McError(st, "mc_prefill_attn_paged_noalloc")
 
 
 def _max_pages(block_tables) -> int:

@@ -21,6 +21,11 @@ mc_status check_params(const mc_attn_params* p) {
   return MC_OK;
 }
 
+float attn_scale_log2e(const mc_attn_params* p) {
+  const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale : 1.0 / std::sqrt((double)p->head_dim);
+  return (float)(scale * 1.4426950408889634);
+}
+
 size_t max_items(const mc_attn_params* p, int32_t batch, int64_t total_new_tokens, int32_t kv_splits) {
   const int64_t G = p->num_q_heads / p->num_kv_heads;
   return (size_t)(p->num_kv_heads * ((total_new_tokens * G) / kAttnTileRows + batch)) * (size_t)kv_splits;

@@ -19,6 +19,9 @@ inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3
 
 mc_status check_params(const mc_attn_params* p);
 
+// softmax scale (0 selects 1 / sqrt(head_dim)) times log2(e): the kernels form probabilities with exp2
+float attn_scale_log2e(const mc_attn_params* p);
+
 // upper bound on work items: per request and KV head, ceil(C_r * G / rows) <= C_r * G / rows + 1
 size_t max_items(const mc_attn_params* p, int32_t batch, int64_t total_new_tokens, int32_t kv_splits = 1);
 

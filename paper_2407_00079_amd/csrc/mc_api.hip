@@ -180,8 +180,7 @@ mc_status launch_planned_attn(const mc_attn_params* p, const mc_attn_plan* plan,
   args.Hkv = p->num_kv_heads;
   args.G = p->num_q_heads / p->num_kv_heads;
   args.max_pages = max_pages_per_req;
-  const double scale = p->softmax_scale > 0.f ? (double)p->softmax_scale : 1.0 / std::sqrt((double)p->head_dim);
-  args.scale_log2e = (float)(scale * 1.4426950408889634);
+  args.scale_log2e = attn_scale_log2e(p);
   args.n_items = plan->n_items;
   args.kv_splits = plan->kv_splits;
   args.rows_total = plan->total_new_tokens * p->num_q_heads;

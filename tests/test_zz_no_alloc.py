@@ -1,0 +1,75 @@
+"""mc_prefill_attn_paged_noalloc (work list built on the device in the library's fixed array: no workspace,
+no allocation, no upload) against mc_prefill_attn_paged, through the C ABI, on calls in a row that share the array."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_00079_amd import binding as B
+from paper_2407_00079_amd import workloads as W
+from gpu_util import DeviceCase, check_close, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def run_both(case):
+    """(out, lse) of the workspace call and of the no-alloc call on the same device tensors"""
+    d = DeviceCase(case)
+    d.run()
+    want_o, want_l = d.out.clone(), d.lse.clone()
+    d.out.fill_(float("nan"))
+    d.lse.fill_(float("nan"))
+    B.mc_prefill_attn_paged_noalloc(d.params, d.q, d.k_pool, d.v_pool, d.block_tables, case.prefix_lens.tolist(),
+                                    case.new_lens.tolist(), d.out, d.lse)
+    torch.cuda.synchronize()
+    return d, want_o, want_l
+
+
+def same(d, want_o, want_l, dtype, what):
+    got_o, got_l = d.out, d.lse
+    assert torch.isfinite(got_o.float()).all() and torch.isfinite(got_l).all(), what
+    # the same kernel over the same work list: bit-identical; the tolerance of the parity tests is the bar
+    check_close(got_o.float().cpu().numpy().astype(np.float64), want_o.float().cpu().numpy().astype(np.float64), dtype, what)
+    assert float((got_l - want_l).abs().max()) <= TOL[dtype]["lse_abs"], what
+    assert torch.equal(got_o, want_o) and torch.equal(got_l, want_l), what
+
+
+def test_two_calls_in_a_row_second_smaller(oracle):
+    # a ragged batch of five requests (several tiles per head, one empty request), then a smaller one: the second call
+    # finds the first call's longer list in the array and must not run any of it
+    big = W.make_attn_case(101, W.BF16, 32, 4, 128, 16, [700, 0, 33, 1500, 260], [300, 77, 0, 130, 1], 512)
+    small = W.make_attn_case(102, W.BF16, 32, 4, 128, 16, [40], [19], 512)
+    for case, name in ((big, "first call"), (small, "second, smaller call")):
+        d, want_o, want_l = run_both(case)
+        same(d, want_o, want_l, W.BF16, name)
+        ref, lse_ref, _ = oracle.case_full(case)
+        check_close(d.out.float().cpu().numpy().astype(np.float64), ref, W.BF16, name + " against the oracle")
+        assert np.abs(d.lse.cpu().numpy() - lse_ref).max() <= TOL[W.BF16]["lse_abs"]
+
+
+def test_fp32_and_many_heads(oracle):
+    case = W.make_attn_case(103, W.F32, 12, 3, 64, 16, [256, 5], [128, 300], 128)
+    d, want_o, want_l = run_both(case)
+    same(d, want_o, want_l, W.F32, "fp32, 3 KV heads")
+    ref, lse_ref, _ = oracle.case_full(case)
+    check_close(d.out.cpu().numpy().astype(np.float64), ref, W.F32, "fp32 against the oracle")
+
+
+def test_limits_and_noops():
+    p = B.attn_params(64, 8, 128, 16, 4096, "bf16")
+    FAKE = 0x7F0000001000
+
+    def call(prefix, new, q=FAKE, out=FAKE, max_pages=1 << 20):
+        n = len(prefix)
+        pl, nl = (ctypes.c_int32 * max(n, 1))(*prefix), (ctypes.c_int32 * max(n, 1))(*new)
+        return B.mc_prefill_attn_paged_noalloc_raw(p, q, FAKE, FAKE, FAKE, max_pages, pl, nl, n, out, None, None)
+
+    assert call([], []) == B.MC_OK
+    assert call([5, 9], [0, 0], q=None, out=None) == B.MC_OK
+    assert call([0] * 129, [1] * 129) == B.MC_ERR_RANGE                     # more requests than the array's table holds
+    assert call([0], [8192 * 16 + 1]) == B.MC_ERR_RANGE                     # 8 heads x 4097 tiles > 32768 items
+    assert call([0], [16], q=None) == B.MC_ERR_NULL
+    assert call([0], [16], out=FAKE + 4) == B.MC_ERR_ALIGN
+    assert call([-1], [16]) == B.MC_ERR_SHAPE
+    assert call([100], [16], max_pages=7) == B.MC_ERR_SHAPE
