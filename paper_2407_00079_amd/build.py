@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libmooncake_hip.so")
 # host_plan.cpp holds no device code: hipcc compiles it as plain C++
-SOURCES = ["mc_api.hip", "host_plan.cpp", "attn_prefill.hip", "attn_noalloc.hip", "kv_copy.hip", "prefix_hash.hip"]
+SOURCES = ["mc_api.hip", "host_plan.cpp", "attn_prefill.hip", "attn_prefill_bf16.hip", "attn_noalloc.hip", "kv_copy.hip", "prefix_hash.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off on purpose (device code only)

@@ -1,18 +1,20 @@
 // Prefix-reused, paged, chunked-prefill attention for gfx950 (paper Section 3,
 // steps 1-2: the uncached tokens of a request attend to the reused prefix pages
 // plus their own pages; the paper gives no kernel, this design is ours).
+// This file: what both dtypes share in structure, the fp32 instantiation (32x32x2 MFMA tiles)
+// and the merge of partial results.  The bf16 instantiation (16x16x32 MFMA tiles, two row
+// tiles per wave) is attn_prefill_bf16.hip; it follows the same plan.
 //
 // Shape of the computation
 //   * A workgroup owns a tile of stacked query rows of one (request, KV head):
 //     row = token * G + head_in_group, so a K/V tile staged once in LDS feeds all
 //     G query heads that share the KV head.  Each wave takes one block of 32 rows.
-//   * Scores are computed TRANSPOSED, S^T = K Q^T, on 32x32 MFMA tiles.  In the
-//     accumulator a lane then owns ONE query column (lane % 32) and 16 keys per
-//     32-key block, so the softmax row reductions are in-lane plus one exchange
-//     between the wave's halves, and exp2(S^T) is already laid out as the B
-//     operand of O^T += V^T P^T.  The key order inside that contraction is the
-//     accumulator's row order; V^T fragments are fetched in the same order with
-//     the LDS transpose read (bf16) or plain row reads (f32).
+//   * Scores are computed TRANSPOSED, S^T = K Q^T, on MFMA tiles.  In the accumulator a
+//     lane then owns query columns and a few keys per 32-key block, so the softmax row
+//     reductions are in-lane plus an exchange between lane groups, and exp2(S^T) is
+//     already laid out as the B operand of O^T += V^T P^T.  The key order inside that
+//     contraction is the accumulator's row order; V^T fragments are fetched in the same
+//     order (bf16: LDS transpose reads; f32: plain row reads).
 //   * The KV loop walks the block table 64 keys (4 pages) at a time.  Tiles are
 //     triple buffered in LDS and filled by direct global->LDS loads (no registers,
 //     no LDS stores; one barrier per tile).  The 16-byte granules of a row are XOR
@@ -32,170 +34,18 @@
 //     at once (the barriers count surviving waves only).
 #include <type_traits>
 
+#include "attn_device.h"
 #include "mc_internal.h"
 
 namespace mc {
 namespace {
 
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-#define MC_LDS __attribute__((address_space(3)))
-
-constexpr int kWaves = 8;              // waves of a workgroup: two per SIMD, 32 stacked rows each
-static_assert(kWaves * 32 == kAttnTileRows, "the host cuts the work list into tiles of kAttnTileRows rows");
-constexpr int kTileKeys = kAttnTileKeys;   // keys per LDS tile = 4 pages of 16
-constexpr int kPageTokens = 16;
-constexpr int kRowBytes = 256;         // one K or V row: 128 bf16 or 64 f32
-constexpr int kPageHeadBytes = kPageTokens * kRowBytes;   // 4 KiB, contiguous in the pool
-constexpr int kKTileBytes = kTileKeys * kRowBytes;        // 16 KiB; rows dense, granules swizzled
-constexpr int kVTileBytes = kTileKeys * kRowBytes;
-constexpr int kBuffers = 3;
-// LDS: the K tiles of the three buffers, then the V tiles.  Every tile starts at a multiple of
-// 16 KiB, so the XOR constants of the swizzle (< 256) never reach a tile base, and the offset of
-// any fragment from its lane's base register stays below the 64 KiB a ds_read immediate can hold.
-constexpr int kVBase = kBuffers * kKTileBytes;
-constexpr float kRescaleSlack = 8.0f;  // log2 units the running max may lag behind
-// stands in for a reference of -inf when probabilities are formed: masked scores (-inf) then give
-// exp2(-inf) = 0 instead of exp2(-inf + inf) = NaN; a row with a finite score has a finite reference
-constexpr float kNoKeyYet = -1e30f;
-
-// Combine a value with the one held by lane ^ 32.  v_permlane32_swap exchanges the upper
-// half of its first register with the lower half of its second, so after it every lane
-// holds its own value in one register and its partner's in the other; max and sum do not
-// care which is which.  Written as asm with two distinct read-write registers (the builtin
-// called with one value for both operands gets its two results merged by the optimiser);
-// the s_nop covers the VALU-write -> permlane read hazard the compiler cannot see.
-__device__ __forceinline__ void swap_halves(float& a, float& b) {
-  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
-}
-__device__ __forceinline__ float max_with_other_half(float x) {
-  float a = x, b = x;
-  swap_halves(a, b);
-  return fmaxf(a, b);
-}
-__device__ __forceinline__ float sum_with_other_half(float x) {
-  float a = x, b = x;
-  swap_halves(a, b);
-  return a + b;
-}
-
-// Direct global -> LDS copy of 16 bytes per lane: lane i's bytes land at lds_base + 16*i
-// (lds_base wave-uniform, it travels in M0).  Written as asm so that the compiler does not
-// know LDS is being written behind its back: it would otherwise make the first LDS read
-// after the copy wait for the copy (vmcnt), which is exactly what the tile pipeline avoids.
-// Ordering is the kernel's own business: s_waitcnt vmcnt(0) + barrier before a tile is read.
-// (M0 is a register the compiler reserves for itself; it sets it right before each of its own
-// uses and has none in this kernel, so naming it as clobbered is all that is needed - the
-// diagnostic about reserved registers in a clobber list is expected here.)
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void dma16(const char* sbase, uint32_t voff, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
-               :: "s"(sbase), "v"(voff), "s"(lds_base) : "m0", "memory");
-}
-__device__ __forceinline__ void dma16(const char* vaddr, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(vaddr), "s"(lds_base) : "m0", "memory");
-}
-#pragma clang diagnostic pop
-
 // ---------------------------------------------------------------------------
 // dtype traits: how fragments are fetched and multiplied
 // ---------------------------------------------------------------------------
+// bf16 rows as the merge kernel writes them (the bf16 attention kernel itself lives in attn_prefill_bf16.hip)
 struct Bf16 {
   static constexpr int kD = 128;
-  static constexpr int kQKSteps = kD / 16;    // mfma 32x32x16 steps over head_dim
-  static constexpr int kPVSteps = 2;          // 16-key steps per 32-key block
-  static constexpr int kDBlocks = kD / 32;
-  typedef bf16x8 frag;
-
-  static __device__ __forceinline__ f32x16 mma(frag a, frag b, f32x16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-  }
-  // B operand: Q[row][16*kk + 8*half .. +7]
-  static __device__ __forceinline__ frag load_q(const char* qrow, int kk, int half) {
-    return *reinterpret_cast<const frag*>(qrow + kk * 32 + half * 16);
-  }
-  // LDS swizzle: 16-byte granule g of tile row r is stored at granule g ^ swz(r).
-  // K: 16 rows read the same logical granule at once -> spread them over all 16 positions.
-  // V: a transpose read touches 4 consecutive rows x 64 B -> rotate the 64-byte quarter by the row.
-  static __device__ __forceinline__ int k_swz(int row) { return row & 15; }
-  static __device__ __forceinline__ int v_swz(int row) { return (row & 3) << 2; }
-  // lane-dependent part of the K fragment address (row r = lane%32, granule 2*kk + half):
-  // r*256 + ((2*kk + half) ^ (r & 15)) * 16  ==  k_lane_off ^ (kk << 5)
-  static __device__ __forceinline__ int k_lane_off(int lane) {
-    const int r = lane & 31, h = lane >> 5;
-    return r * kRowBytes + (((r >> 1) & 7) << 5) + ((h ^ (r & 1)) << 4);
-  }
-  // A operand: K[32*kb + lane%32][16*kk + 8*half .. +7]; kx[kk] = lane base ^ (kk << 5), off = tile + block offset
-  static constexpr int kKX = kQKSteps;
-  static __device__ __forceinline__ uint32_t k_xor(int i) { return (uint32_t)(i << 5); }
-  static __device__ __forceinline__ frag load_k(const uint32_t (&kx)[kKX], int off, int kk) {
-    return *reinterpret_cast<MC_LDS const frag*>(kx[kk] + off);
-  }
-  // A operand of O^T += V^T P^T: V[key(e)][db*32 + lane%32] for the 8 keys
-  // 32*kb + 16*step + 8*(e/4) + 4*half + e%4, i.e. two groups of 4 consecutive keys.
-  // The transpose read returns, to lane i of a 16-lane group, element i%4 of lanes
-  // i/4, 4+i/4, 8+i/4, 12+i/4: source lane s must address key s/4, columns 4*(s%4)..+3.
-  // With the swizzle, granule 4*db + gl of row r sits at ((db ^ (r & 3)) << 2) + gl, so the address
-  // is v_lane_off ^ (db << 6) plus a row offset that is a multiple of 4 rows.
-  static __device__ __forceinline__ int v_lane_off(int lane) {
-    const int s = lane & 15;
-    const int r = (lane >> 5) * 4 + (s >> 2);
-    const int col_bytes = (((lane >> 4) & 1) * 16 + (s & 3) * 4) * 2;   // < 64
-    return r * kRowBytes + ((r & 3) << 6) + col_bytes;
-  }
-  static constexpr int kVX = kDBlocks;
-  static __device__ __forceinline__ uint32_t v_xor(int i) { return (uint32_t)(i << 6); }
-  // vx[db] = lane base ^ (db << 6), off = tile + block offset
-  static __device__ __forceinline__ frag load_v(const uint32_t (&vx)[kVX], int off, int step, int db) {
-    const uint32_t p = vx[db] + off + step * 16 * kRowBytes;
-    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(uintptr_t)(p));
-    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(uintptr_t)(p + 8 * kRowBytes));
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  }
-  // A block's probabilities as P V multiplies them: rounded to bf16, fragment `step` holds the
-  // accumulator registers 8*step .. 8*step+7 (the B operand of that 16-key step).
-  struct pblock { frag f[kPVSteps]; };
-  static __device__ __forceinline__ pblock round_p(const f32x16& p) {
-    pblock b;
-#pragma unroll
-    for (int st = 0; st < kPVSteps; ++st)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) b.f[st][e] = (__bf16)p[st * 8 + e];
-    return b;
-  }
-  static __device__ __forceinline__ frag p_frag(const pblock& b, int step) { return b.f[step]; }
-  // round probabilities e0, e0+1 into their fragment and add the ROUNDED values to acc (one
-  // v_cvt_pk_bf16_f32, one v_dot2c_f32_bf16)
-  template <int N>
-  static __device__ __forceinline__ float round_sum(pblock& b, const f32x16& p, int e0, float acc) {
-    static_assert(N == 2, "bf16 probabilities are rounded in pairs");
-    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    const bf16x2 pr = {(__bf16)p[e0], (__bf16)p[e0 + 1]};
-    b.f[e0 >> 3][e0 & 7] = pr[0];
-    b.f[e0 >> 3][(e0 & 7) + 1] = pr[1];
-    return __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
-  }
-  // sum of the 16 ROUNDED probabilities, two per v_dot2c_f32_bf16 with fp32 accumulation
-  static __device__ __forceinline__ float block_sum(const pblock& b) {
-    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    float acc = 0.f;
-#pragma unroll
-    for (int st = 0; st < kPVSteps; ++st)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const bf16x2 pr = {b.f[st][2 * e], b.f[st][2 * e + 1]};
-        acc = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
-      }
-    return acc;
-  }
   // four consecutive output columns
   static __device__ __forceinline__ void store4(char* orow, int col, float a, float b, float c, float d) {
     bf16x4 v;
@@ -752,13 +602,9 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
 hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream) {
   (void)hipGetLastError();   // drop any stale error of earlier, unrelated runtime calls
   const bool split = args.kv_splits > 0;
-  if (dtype == MC_DTYPE_BF16) {
-    if (split) attn_prefill_kernel<Bf16, kWaves, true><<<args.n_items, kWaves * 64, 0, stream>>>(args);
-    else attn_prefill_kernel<Bf16, kWaves, false><<<args.n_items, kWaves * 64, 0, stream>>>(args);
-  } else {
-    if (split) attn_prefill_kernel<F32, kWaves, true><<<args.n_items, kWaves * 64, 0, stream>>>(args);
-    else attn_prefill_kernel<F32, kWaves, false><<<args.n_items, kWaves * 64, 0, stream>>>(args);
-  }
+  if (dtype == MC_DTYPE_BF16) return launch_attn_bf16(args, stream);
+  if (split) attn_prefill_kernel<F32, kWaves, true><<<args.n_items, kWaves * 64, 0, stream>>>(args);
+  else attn_prefill_kernel<F32, kWaves, false><<<args.n_items, kWaves * 64, 0, stream>>>(args);
   return hipGetLastError();
 }
 

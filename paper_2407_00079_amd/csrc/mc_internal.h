@@ -31,6 +31,9 @@ struct AttnArgs {
 // enqueue the attention kernel over args.n_items work items
 hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream);
 
+// the bf16 instantiation (attn_prefill_bf16.hip), reached through launch_attn
+hipError_t launch_attn_bf16(const AttnArgs& args, hipStream_t stream);
+
 // enqueue the merge of kv_splits partial results over `rows` rows into out (dtype) and lse (or null)
 hipError_t launch_attn_merge(int dtype, const float* o_parts, const float* lse_parts, int kv_splits, int64_t rows,
                              void* out, float* lse, hipStream_t stream);
