@@ -2,21 +2,26 @@
 """Benchmark of the KVCache-reuse hot path on one MI355X.
 
 One step = one layer of layer-wise prefill (paper Section 5.2) on two HIP streams:
-  copy stream:    mc_kv_unpack_layer(l)  (load the layer's KV pages into the paged pool)
-  compute stream: wait load(l) -> mc_kv_append_paged (the chunk's new K/V rows into their pages)
-                  -> mc_prefill_attn_paged (the attention workload)
+  copy stream:    mc_kv_unpack_layer(l + 1)  (load the next layer's KV pages into its paged pool)
+  compute stream: wait load(l) -> mc_kv_append_run (the chunk's new K/V rows into their pages)
+                  -> mc_prefill_attn_run (the attention workload)
   copy stream:    wait attention(l) -> mc_kv_pack_layer(l)  (store the layer's pages)
-The attention workload is configuration 2 (64/8 heads, head_dim 128, bf16, 8192 reused
-prefix tokens + 8192 new tokens); the page traffic is one layer of configuration 5
-(2048 pages of 32 KiB for K and for V, each direction).  Inputs are seeded synthetic
-tensors, resident in HBM before the timed region.
+The attention workload of the headline is configuration 3, the long-context shape the target is stated on
+(one GPU's tensor-parallel share of a 128k-token prompt: 8 query heads / 1 KV head, head_dim 128, bf16,
+122880 reused prefix tokens + 8192 new tokens); the page traffic is one layer of configuration 5 (2048 pages
+of 32 KiB for K and for V, each direction).  Inputs are seeded synthetic tensors, resident in HBM before the
+timed region.
 
-Prints ONE JSON line.  `value` is attention TFLOP/s over the whole timed region
-(visible query-key pairs only, both contractions), with the page traffic overlapped.
+Prints ONE JSON line.  `value` is attention TFLOP/s over the whole timed region (visible query-key pairs
+only, both contractions), with the page traffic overlapped.  Further fields: the roofline of every kernel,
+the same step with configuration 2's attention, isolated kernels, what the board sustains for MFMAs alone
+and for plain copies (bench_probes.hip), the step against a host-memory pool, and the CPU oracle timed on a
+bounded sample.
 """
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -27,8 +32,9 @@ MFMA_BF16_PEAK_TFLOPS = 2516.6   # 256 CU x 4 SIMD x 1024 flop/cycle x 2.4 GHz
 HBM_PEAK_GBS = 8000.0
 
 
-def measured_traffic():
-    """HBM bytes per launch from the committed rocprofv3 counter summary (None if it is absent)."""
+def committed_traffic():
+    """HBM bytes per launch from the committed rocprofv3 counter summary ({} if it is absent).  Counters cannot be
+    read inside a timed run: the figures are those of the profile named in the output."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic_bench_step.txt")
     out = {}
     try:
@@ -41,20 +47,22 @@ def measured_traffic():
     return out
 
 
-def mfma_ceiling():
-    """Rate of back-to-back bf16 MFMAs alone on this board (zeros / ones / random operands), measured by the
-    stand-alone program bench_probes.hip; None when it is missing or fails."""
-    import subprocess
+def probe(mode):
+    """One mode of the stand-alone measurement program bench_probes.hip (None when it is missing or fails)."""
     exe = os.path.join(ROOT, "bench_probes")
     try:
         if not os.path.exists(exe):
             import __graft_entry__
             __graft_entry__.build_bench_probes()
-        out = subprocess.run([exe], capture_output=True, text=True, timeout=60, check=True).stdout.split()
-        return {out[i]: {"tflops": float(out[i + 1]), "shader_mhz": float(out[i + 2])} for i in (0, 3, 6)}
+        return json.loads(subprocess.run([exe, mode], capture_output=True, text=True, timeout=120, check=True).stdout)
     except Exception as e:      # measurement aid only: the benchmark goes on without it
-        sys.stderr.write(f"mfma_ceiling unavailable: {e}\n")
+        sys.stderr.write(f"bench_probes {mode} unavailable: {e}\n")
         return None
+
+
+LABELS = {2: "config 2: 64/8 heads, P=8192, C=8192 (16k prompt, half cached)",
+          3: "config 3: 8/1 heads, P=122880, C=8192 (last chunk of a 128k prompt, one GPU's tensor-parallel share)",
+          4: "config 4: 16 requests, 64/8 heads, prefixes U[0,32768] (page multiples), chunks lognormal(median 2048)"}
 
 
 def main():
@@ -62,11 +70,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--attn-config", type=int, default=2, choices=(2, 3, 4),
-                    help="attention workload of the step (default: configuration 2)")
+    ap.add_argument("--attn-config", type=int, default=3, choices=(2, 3, 4),
+                    help="attention workload of the headline step (default: configuration 3, the 128k-context shape)")
     ap.add_argument("--layers", type=int, default=8, help="distinct per-layer pools the steps cycle through")
-    ap.add_argument("--cpu-rows", type=int, default=65536, help="rows the CPU oracle is timed on (0 = skip)")
-    ap.add_argument("--no-extra", action="store_true", help="skip the isolated / configuration-3 measurements")
+    ap.add_argument("--cpu-rows", type=int, default=8192, help="rows the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-extra", action="store_true", help="only the headline step")
     ap.add_argument("--zero-inputs", action="store_true",
                     help="DIAGNOSTIC, not a measurement of the workload: Q, K and V all zero (same kernels, same "
                          "instruction stream, no operand bit activity) to show what the board's power limit costs")
@@ -87,6 +95,18 @@ def main():
     def to_dev(a):
         a = np.ascontiguousarray(a)
         return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
+
+    def timed_loop(fn, reps, warm, stream):
+        """microseconds per call of fn, `reps` calls back to back on `stream` (launch gaps included)"""
+        for _ in range(warm):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(reps):
+            fn()
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / reps
 
     class Attn:
         def __init__(self, idx):
@@ -111,12 +131,17 @@ def main():
             if args.zero_inputs:
                 for t in (self.q, self.k, self.v, self.k_new, self.v_new):
                     t.zero_()
-
             # work list and request table: prepared and uploaded once per batch, as a prefill pass would for all of
             # its layers; append and attention of every step then only launch their kernels
             self.plan = B.mc_prefill_attn_prepare(self.params, self.pl, self.nl, 0, self.ws)
             self.ws_one_shot = torch.empty_like(self.ws)
             torch.cuda.synchronize()          # the upload has landed before any stream runs from the plan
+
+        def label(self):
+            c = self.case
+            return (f"config {self.idx} attention (P={self.pl if len(self.pl) < 3 else 'varlen'}, "
+                    f"C={self.nl if len(self.nl) < 3 else 'varlen'}, {c.num_q_heads}/{c.num_kv_heads} heads, D=128, "
+                    f"16-token pages scattered over {c.num_pages} pool pages)")
 
         def append(self, stream):
             B.mc_kv_append_run(self.params, self.plan, self.k_new, self.v_new, self.k, self.v, self.bt, self.ws, stream)
@@ -143,14 +168,18 @@ def main():
             ms = sorted(a.elapsed_time(b) for a, b in ev)
             return ms[len(ms) // 2], ms[0]
 
-    attn = Attn(args.attn_config)
+        def free(self):
+            for name in ("q", "k", "v", "out", "k_new", "v_new", "lse"):
+                delattr(self, name)
+            torch.cuda.empty_cache()
 
     # ---- one layer's page traffic (configuration 5), `layers` distinct pool sets so steps do not hit in cache
     sh = W.config_shapes(5)
-    n, pb, N1, N2 = sh["n"], sh["page_bytes"], sh["num_pages"], sh["num_pages_dst"]
+    n, pb, N2 = sh["n"], sh["page_bytes"], sh["num_pages_dst"]
     rng = np.random.default_rng(sh["seed"])
-    src_ids = to_dev(rng.permutation(N1)[:n].astype(np.int32))
-    dst_ids = to_dev(rng.permutation(N2)[:n].astype(np.int32))
+    rng.permutation(sh["num_pages"])          # the source permutation of the recipe (drawn, unused here)
+    dst_ids_host = rng.permutation(N2)[:n].astype(np.int32)
+    dst_ids = to_dev(dst_ids_host)
     gen = torch.Generator(device=dev)
     gen.manual_seed(sh["seed"])
     LAY = args.layers
@@ -179,7 +208,7 @@ def main():
     def pack(l, stream):
         B.mc_kv_pack_layer(k_pool[l], v_pool[l], N2, pb, dst_ids, n, k_store[l], v_store[l], stream)
 
-    def run_steps(count, timed):
+    def run_steps(attn, count, timed):
         """Layer-wise schedule: load(l+1) is in flight while attention(l) runs; store(l) follows attention(l)."""
         marks, copy_marks = [], {"unpack": [], "pack": []}
 
@@ -220,71 +249,69 @@ def main():
                 timed_copy("pack", pack, l)
         return marks, copy_marks
 
-    run_steps(Wm, False)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    marks, copy_marks = run_steps(K, True)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / K
-    attn_ms = sorted(a.elapsed_time(b) for a, b in marks)
-    attn_ms_avg = sum(attn_ms) / len(attn_ms)
-    value = attn.flops / (ms_per_step * 1e-3) / 1e12
-    traffic = measured_traffic()
+    def time_steps(attn):
+        run_steps(attn, Wm, False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        marks, copy_marks = run_steps(attn, K, True)
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / K
+        attn_ms = [a.elapsed_time(b) for a, b in marks]
+        in_step = {}
+        for name, ms in copy_marks.items():
+            us = sorted(a.elapsed_time(b) * 1e3 for a, b in ms)
+            if us:
+                in_step[name] = {"us_median": round(us[len(us) // 2], 2), "us_min": round(us[0], 2), "us_max": round(us[-1], 2)}
+        return ms_per_step, attn_ms, in_step
+
+    traffic = committed_traffic()
 
     def hbm(prefix):
         r, w = traffic.get(prefix + "_read_bytes"), traffic.get(prefix + "_write_bytes")
-        return None if r is None or w is None else {"bytes": r + w, "read_bytes": r, "write_bytes": w, "unit": "B per launch",
-                                                    "source": "profiles/hbm_traffic_bench_step.txt"}
+        return None if r is None or w is None else {
+            "bytes": r + w, "read_bytes": r, "write_bytes": w, "unit": "B per launch",
+            "source": "committed rocprofv3 counter summary profiles/hbm_traffic_bench_step.txt (FETCH_SIZE / WRITE_SIZE "
+                      "calibrated on a plain copy), not counted in this run"}
 
+    def attn_roofline(attn, attn_ms):
+        avg = sum(attn_ms) / len(attn_ms)
+        tf = attn.flops / (avg * 1e-3) / 1e12
+        return {"kernel": "attn_prefill_bf16_kernel", "bound": "mfma", "achieved": round(tf, 2),
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                "avg_launch_ms": round(avg, 4), "min_launch_ms": round(min(attn_ms), 4),
+                "launch_ms": [round(x, 3) for x in attn_ms], "flops_per_launch": attn.flops,
+                "traffic": hbm(f"attn_config{attn.idx}")}
+
+    # ---- the headline step
+    attn = Attn(args.attn_config)
+    ms_per_step, attn_ms, in_step = time_steps(attn)
+    value = attn.flops / (ms_per_step * 1e-3) / 1e12
+    step_what = ("preceded by the append of its chunk's K/V rows (work list prepared once per batch: "
+                 "mc_prefill_attn_prepare, then mc_kv_append_run + mc_prefill_attn_run per step), + one config-5 layer of "
+                 "KV unpack and pack (2048 pages x 32 KiB, K and V) on a second stream")
     result = {
         "metric": "prefill attn TFLOP/s (% MFMA peak); KV pack/unpack GB/s (% HBM peak)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic" if not args.zero_inputs else "ALL-ZERO tensors: power diagnostic, not the workload",
-        "config": {"workload": f"config {args.attn_config} attention "
-                               f"(P={attn.pl if len(attn.pl) < 3 else 'varlen'}, C={attn.nl if len(attn.nl) < 3 else 'varlen'}, "
-                               f"{attn.case.num_q_heads}/{attn.case.num_kv_heads} heads, D=128, 16-token pages) "
-                               f"preceded by the append of its chunk's K/V rows (work list prepared once per batch: "
-                               f"mc_prefill_attn_prepare, then mc_kv_append_run + mc_prefill_attn_run per step), "
-                               f"+ one config-5 layer of KV unpack and pack (2048 pages x 32 KiB, K and V) on a second stream",
+        "config": {"workload": f"{attn.label()} {step_what}",
                    "attn_flops_per_step": attn.flops, "copy_bytes_per_step": 2 * copy_bytes},
         "pct_mfma_peak": round(100 * value / MFMA_BF16_PEAK_TFLOPS, 2),
-        "roofline": {"kernel": "attn_prefill_kernel<Bf16>", "bound": "mfma",
-                     "achieved": round(attn.flops / (attn_ms_avg * 1e-3) / 1e12, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s",
-                     "frac": round(attn.flops / (attn_ms_avg * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "avg_launch_ms": round(attn_ms_avg, 4), "min_launch_ms": round(attn_ms[0], 4),
-                     "launch_ms": [round(a.elapsed_time(b), 3) for a, b in marks],
-                     "traffic": hbm("attn_config2") if args.attn_config == 2 else None},
+        "roofline": attn_roofline(attn, attn_ms),
+        "copies_in_step": in_step,
     }
 
-    # the copies as they ran inside the step, beside the attention of the neighbouring layer
-    in_step = {}
-    for name, ms in copy_marks.items():
-        us = sorted(a.elapsed_time(b) * 1e3 for a, b in ms)
-        if us:
-            in_step[name] = {"us_median": round(us[len(us) // 2], 2), "us_min": round(us[0], 2), "us_max": round(us[-1], 2)}
-    result["copies_in_step"] = in_step
-
     if not args.no_extra:
+        s = torch.cuda.current_stream()
         # isolated kernels, same inputs, nothing else running
         med, mn = attn.time_isolated()
         result["attn_isolated"] = {"config": args.attn_config, "ms_median": round(med, 4), "ms_min": round(mn, 4),
                                    "tflops": round(attn.flops / (med * 1e-3) / 1e12, 2),
                                    "pct_mfma_peak": round(100 * attn.flops / (med * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2)}
-        s = torch.cuda.current_stream()
         # the one-shot call (list built and uploaded inside every call), back to back like the isolated runs
-        for _ in range(3):
-            attn.launch_one_shot(s)
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record(s)
-        for _ in range(10):
-            attn.launch_one_shot(s)
-        b.record(s)
-        torch.cuda.synchronize()
-        result["attn_one_shot_call"] = {"ms_per_call_back_to_back": round(a.elapsed_time(b) / 10, 4),
+        us = timed_loop(lambda: attn.launch_one_shot(s), 10, 3, s)
+        result["attn_one_shot_call"] = {"ms_per_call_back_to_back": round(us / 1e3, 4),
                                         "what": "mc_prefill_attn_paged: prepare + run in one call"}
 
         def pack_ordered(l, stream):
@@ -294,23 +321,16 @@ def main():
         # two combinations are measured for comparison: the write side is the one that wants to be sequential
         for name, fn in (("pack", pack), ("unpack", unpack), ("pack_pool_order", pack_ordered),
                          ("unpack_list_order", unpack_list_order)):
-            for l in range(LAY):
-                fn(l, s)
-            reps = 80
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(s)
-            for i in range(reps):           # 80 layers back to back, launch gaps included
-                fn(i % LAY, s)
-            b.record(s)
-            torch.cuda.synchronize()
-            us = a.elapsed_time(b) * 1e3 / reps
+            it = iter(range(10 ** 9))
+            us = timed_loop(lambda: fn(next(it) % LAY, s), 80, LAY, s)      # 80 layers back to back, launch gaps included
             gbs = copy_bytes / (us * 1e-6) / 1e9
             result[f"roofline_{name}"] = {"kernel": f"kv_copy_kernel<{name.split('_')[0]}>", "bound": "hbm", "achieved": round(gbs, 1),
                                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                                           "us_per_layer": round(us, 2), "bytes_per_launch": copy_bytes,
                                           "traffic": hbm(name.split("_")[0])}
         # what a copy of the same bytes reaches on this board with nothing scattered: the same kernel with the pages
-        # in pool order (ids 0 .. n-1), and the runtime's device-to-device copy
+        # in pool order (ids 0 .. n-1), the runtime's device-to-device copy, and the stand-alone probes: the read-only
+        # and write-only halves of the access pattern, fixed cost per launch and steady-state rate
         seq_ids = torch.arange(n, dtype=torch.int32, device=dev)
 
         def pack_contiguous(l, stream):
@@ -322,38 +342,27 @@ def main():
 
         ceiling = {}
         for name, fn in (("same_kernel_contiguous", pack_contiguous), ("runtime_d2d_copy", runtime_copy)):
-            for l in range(LAY):
-                fn(l, s)
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(s)
-            for i in range(80):
-                fn(i % LAY, s)
-            b.record(s)
-            torch.cuda.synchronize()
-            us = a.elapsed_time(b) * 1e3 / 80
+            it = iter(range(10 ** 9))
+            us = timed_loop(lambda: fn(next(it) % LAY, s), 80, LAY, s)
             ceiling[name] = {"GBs": round(copy_bytes / (us * 1e-6) / 1e9, 1), "us_per_layer": round(us, 2),
                              "frac_hbm_peak": round(copy_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
         result["copy_ceiling"] = {"what": "the same 2 x 64 MiB read and written with no scatter at all", **ceiling}
         # append of the step's chunk alone, launched back to back
         c = attn.case
-        for _ in range(5):
-            attn.append(s)
-        reps = 80
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record(s)
-        for i in range(reps):
-            attn.append(s)
-        b.record(s)
-        torch.cuda.synchronize()
-        us = a.elapsed_time(b) * 1e3 / reps
+        us = timed_loop(lambda: attn.append(s), 80, 5, s)
         ab = 2 * 2 * c.total_new * c.num_kv_heads * c.head_dim * 2
         result["roofline_append"] = {"kernel": "kv_append_kernel", "bound": "hbm",
                                      "achieved": round(ab / (us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                      "frac": round(ab / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "us_per_launch": round(us, 2),
                                      "bytes_per_launch": ab, "traffic": None,
                                      "note": "same buffers every launch: the working set fits the 256 MiB last-level cache"}
-        # the same layer-wise step against the HOST pool: a layer's pages come from pinned host memory before its
-        # attention and go back after it (load on one side stream, store on another, attention on the compute stream)
+
+        # ---- the same layer-wise step against the HOST pool (Section 3 steps 1 and 3): a layer's pages come from pinned
+        # host memory before its attention and go back after it (load on one side stream, store on another, append +
+        # attention on the compute stream).  Two traffic models: `prefix_and_chunk` is the paper's flow for a request
+        # of configuration 5's size with half of it cached, as its simulated prompts are (the 1024 reused prefix
+        # pages are loaded, the 1024 pages the new tokens filled are stored); `all_pages` moves all 2048 pages in
+        # both directions.
         HL = min(4, LAY)
         kh_in = [torch.empty((n, pb), dtype=torch.uint8, pin_memory=True) for _ in range(HL)]
         vh_in = [torch.empty((n, pb), dtype=torch.uint8, pin_memory=True) for _ in range(HL)]
@@ -362,33 +371,51 @@ def main():
         for t in kh_in + vh_in:
             t.random_(0, 256)
         st_load, st_store = torch.cuda.Stream(), torch.cuda.Stream()
+        half = n // 2
+        ids_prefix, ids_chunk = dst_ids[:half].contiguous(), dst_ids[half:].contiguous()
 
-        def host_steps(count):
+        def host_steps(count, load_ids, n_load, store_ids, n_store):
             loaded = [torch.cuda.Event() for _ in range(count + 1)]
             attended = [torch.cuda.Event() for _ in range(count)]
-            B.mc_kv_load_layer(kh_in[0], vh_in[0], k_remote[0], v_remote[0], N2, pb, dst_ids, n, k_pool[0], v_pool[0],
-                               st_load)
-            loaded[0].record(st_load)
+            stored = {}
+
+            def load(i):
+                ln = i % HL
+                if ln in stored:                     # the pools of this layer are still being stored from
+                    st_load.wait_event(stored[ln])
+                B.mc_kv_load_layer(kh_in[ln], vh_in[ln], k_remote[ln], v_remote[ln], N2, pb, load_ids, n_load, k_pool[ln],
+                                   v_pool[ln], st_load)
+                loaded[i].record(st_load)
+
+            load(0)
             for i in range(count):
-                l, ln = i % HL, (i + 1) % HL
+                l = i % HL
                 if i + 1 < count:
-                    B.mc_kv_load_layer(kh_in[ln], vh_in[ln], k_remote[ln], v_remote[ln], N2, pb, dst_ids, n, k_pool[ln],
-                                       v_pool[ln], st_load)
-                    loaded[i + 1].record(st_load)
+                    load(i + 1)
                 compute.wait_event(loaded[i])
                 attn.append(compute)
                 attn.launch(compute)
                 attended[i].record(compute)
                 st_store.wait_event(attended[i])
-                B.mc_kv_store_layer(k_pool[l], v_pool[l], N2, pb, dst_ids, n, k_store[l], v_store[l], kh_out[l],
+                B.mc_kv_store_layer(k_pool[l], v_pool[l], N2, pb, store_ids, n_store, k_store[l], v_store[l], kh_out[l],
                                     vh_out[l], st_store)
+                stored[l] = torch.cuda.Event()
+                stored[l].record(st_store)
 
-        host_steps(4)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        host_steps(12)
-        torch.cuda.synchronize()
-        ms_host = (time.perf_counter() - t0) * 1e3 / 12
+        host = {"what": "the step with each layer's pages loaded from and stored to pinned host memory: load and store on "
+                        "two side streams, append + attention on the compute stream; a load waits for the last store "
+                        "that read the same pools"}
+        for name, (li, nl_, si, ns_) in (("prefix_and_chunk", (ids_prefix, half, ids_chunk, n - half)),
+                                         ("all_pages", (dst_ids, n, dst_ids, n))):
+            host_steps(4, li, nl_, si, ns_)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            host_steps(12, li, nl_, si, ns_)
+            torch.cuda.synchronize()
+            ms_host = (time.perf_counter() - t0) * 1e3 / 12
+            host[name] = {"ms_per_step": round(ms_host, 4), "attn_tflops": round(attn.flops / (ms_host * 1e-3) / 1e12, 1),
+                          "load_bytes_per_layer": 2 * nl_ * pb, "store_bytes_per_layer": 2 * ns_ * pb,
+                          "vs_step_in_hbm": round(ms_host / ms_per_step, 3)}
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         ev[0].record(st_load)
         for l in range(HL):
@@ -401,17 +428,13 @@ def main():
         ev[3].record(st_store)
         torch.cuda.synchronize()
         layer_bytes = 2 * n * pb
-        result["host_streaming"] = {
-            "what": "the step with each layer's 2048 pages (K and V, 32 KiB each) loaded from and stored to pinned host "
-                    "memory: load and store on two side streams, append + attention on the compute stream",
-            "ms_per_step": round(ms_host, 4), "attn_tflops": round(attn.flops / (ms_host * 1e-3) / 1e12, 1),
-            "load_layer_ms_alone": round(ev[0].elapsed_time(ev[1]) / HL, 3),
-            "load_GBs_alone": round(layer_bytes / (ev[0].elapsed_time(ev[1]) / HL * 1e-3) / 1e9, 1),
-            "store_layer_ms_alone": round(ev[2].elapsed_time(ev[3]) / HL, 3),
-            "store_GBs_alone": round(layer_bytes / (ev[2].elapsed_time(ev[3]) / HL * 1e-3) / 1e9, 1),
-            "bytes_per_layer_per_direction": layer_bytes}
+        host["link_alone"] = {"load_GBs": round(layer_bytes / (ev[0].elapsed_time(ev[1]) / HL * 1e-3) / 1e9, 1),
+                              "store_GBs": round(layer_bytes / (ev[2].elapsed_time(ev[3]) / HL * 1e-3) / 1e9, 1),
+                              "bytes_per_layer_per_direction": layer_bytes}
+        result["host_streaming"] = host
         del kh_in, vh_in, kh_out, vh_out
-        # prefix keys of a batch of long prompts and their match against 16 instances' cache keys
+
+        # ---- prefix keys of a batch of long prompts and their match against 16 instances' cache keys
         NP, LP, BT, NI, NC = 64, 131072, 512, 16, 200000
         g3 = torch.Generator(device=dev)
         g3.manual_seed(20240707)
@@ -442,39 +465,38 @@ def main():
         prefix = {"workload": f"{NP} prompts x {LP} tokens, {BT}-token blocks; {NI} instances of ~{NC + NP * 136} keys"}
         for name, fn in (("hash", lambda: B.mc_prefix_hash(toks, toff, BT, pkeys, ws_h, s)),
                          ("match", lambda: B.mc_prefix_match(pkeys, koff, ckeys, coff, plen, bl, bi, ws_m, s))):
-            for _ in range(3):
-                fn()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(s)
-            for _ in range(20):
-                fn()
-            b.record(s)
-            torch.cuda.synchronize()
-            us = a.elapsed_time(b) * 1e3 / 20
-            prefix[name] = {"us": round(us, 1)}
+            prefix[name] = {"us": round(timed_loop(fn, 20, 3, s), 1)}
         prefix["hash"]["GBs"] = round(4 * NP * LP / (prefix["hash"]["us"] * 1e-6) / 1e9, 1)
         prefix["hash"]["frac_hbm_peak"] = round(prefix["hash"]["GBs"] / HBM_PEAK_GBS, 4)
         prefix["match"]["lookups_per_s"] = round(nkeys * NI / (prefix["match"]["us"] * 1e-6), 0)
         prefix["match"]["best_len_of_request_0"] = int(bl[0].item())
         result["prefix_keys"] = prefix
         del toks, pkeys, ckeys, caches
-        labels = {3: "config 3: 8/1 heads, P=122880, C=8192 (128k context)",
-                  4: "config 4: 16 requests, 64/8 heads, prefixes U[0,32768] (page multiples), chunks lognormal(median 2048)"}
-        del attn.q, attn.k, attn.v, attn.out, attn.k_new, attn.v_new
-        for idx in (3, 4):
+
+        # ---- the other attention configurations: configuration 2 inside the same step (configuration 5 of the
+        # recipe names this pairing), the rest isolated
+        attn.free()
+        for idx in (2, 3, 4):
             if idx == args.attn_config:
                 continue
             other = Attn(idx)
             med, mn = other.time_isolated()
-            result[f"attn_config{idx}"] = {"workload": labels[idx], "flops": other.flops, "ms_median": round(med, 4),
+            result[f"attn_config{idx}"] = {"workload": LABELS[idx], "flops": other.flops, "ms_median": round(med, 4),
                                           "ms_min": round(mn, 4), "tflops": round(other.flops / (med * 1e-3) / 1e12, 2),
                                           "pct_mfma_peak": round(100 * other.flops / (med * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2)}
+            if idx == 2:
+                ms2, attn_ms2, in_step2 = time_steps(other)
+                result["step_config2"] = {
+                    "workload": f"{other.label()} {step_what}", "ms_per_step": round(ms2, 4),
+                    "value_tflops": round(other.flops / (ms2 * 1e-3) / 1e12, 2),
+                    "pct_mfma_peak": round(100 * other.flops / (ms2 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
+                    "roofline": attn_roofline(other, attn_ms2), "copies_in_step": in_step2}
+            other.free()
             del other
-            torch.cuda.empty_cache()
 
-    if not args.no_extra:
-        def whole_vs_split(P2, C2, Hq2, Hkv2, iters):
-            """Whole-row kernel against the slice count the library suggests + merge, one request."""
+        def default_entry_forms(P2, C2, Hq2, Hkv2, iters):
+            """mc_prefill_attn_paged with the minimal workspace (whole rows), with a workspace that has room for
+            partial results (the call takes key slices by itself), and the explicit split + merge calls."""
             npg = (P2 + C2) // 16
             g2 = torch.Generator(device=dev)
             g2.manual_seed(20240706)
@@ -487,6 +509,7 @@ def main():
             out2 = torch.empty_like(q2)
             ws_a = torch.empty(B.mc_prefill_attn_workspace_bytes(prm, 1, C2), dtype=torch.uint8, device=dev)
             ws_b = torch.empty(B.mc_prefill_attn_split_workspace_bytes(prm, 1, C2, SP), dtype=torch.uint8, device=dev)
+            ws_c = torch.empty(B.mc_prefill_attn_auto_workspace_bytes(prm, [P2], [C2]), dtype=torch.uint8, device=dev)
             o_parts = torch.empty(SP, C2, Hq2, 128, device=dev, dtype=torch.float32)
             l_parts = torch.empty(SP, C2, Hq2, device=dev, dtype=torch.float32)
             s = torch.cuda.current_stream()
@@ -494,22 +517,20 @@ def main():
             def whole():
                 B.mc_prefill_attn_paged(prm, q2, k2, v2, bt2, [P2], [C2], out2, None, ws_a, s)
 
+            def default_roomy():
+                B.mc_prefill_attn_paged(prm, q2, k2, v2, bt2, [P2], [C2], out2, None, ws_c, s)
+
             def split():
                 B.mc_prefill_attn_paged_split(prm, q2, k2, v2, bt2, [P2], [C2], SP, o_parts, l_parts, ws_b, s)
                 B.mc_attn_merge_lse(o_parts, l_parts, SP, C2 * Hq2, 128, B.MC_DTYPE_BF16, out2, None, s)
 
             fl2 = 4 * 128 * Hq2 * (C2 * P2 + C2 * (C2 + 1) // 2)
-            rec = {"workload": f"{Hq2}/{Hkv2} heads, P={P2}, C={C2}", "flops": fl2}
-            for name, fn in (("whole_row", whole), (f"split{SP}_plus_merge", split)):
-                for _ in range(3):
-                    fn()
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record(s)
-                for _ in range(iters):
-                    fn()
-                b.record(s)
-                torch.cuda.synchronize()
-                us = a.elapsed_time(b) * 1e3 / iters
+            rec = {"workload": f"{Hq2}/{Hkv2} heads, P={P2}, C={C2}", "flops": fl2, "suggested_key_slices": SP,
+                   "workspace_bytes": {"minimal": ws_a.numel(), "with_room_for_partials": ws_c.numel()}}
+            for name, fn in (("mc_prefill_attn_paged_minimal_workspace", whole),
+                             ("mc_prefill_attn_paged_roomy_workspace", default_roomy),
+                             (f"explicit_split{SP}_plus_merge", split)):
+                us = timed_loop(fn, iters, 3, s)
                 rec[name] = {"us": round(us, 1), "tflops": round(fl2 / (us * 1e-6) / 1e12, 1)}
             return rec
 
@@ -527,41 +548,43 @@ def main():
             out2 = torch.empty_like(q2)
             ws2 = torch.empty(B.mc_prefill_attn_workspace_bytes(prm, 1, C2), dtype=torch.uint8, device=dev)
             s2 = torch.cuda.current_stream()
-            for _ in range(2):
-                B.mc_prefill_attn_paged(prm, q2, k2, v2, bt2, [P2], [C2], out2, None, ws2, s2)
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(s2)
-            for _ in range(5):
-                B.mc_prefill_attn_paged(prm, q2, k2, v2, bt2, [P2], [C2], out2, None, ws2, s2)
-            b.record(s2)
-            torch.cuda.synchronize()
-            ms = a.elapsed_time(b) / 5
+            us = timed_loop(lambda: B.mc_prefill_attn_paged(prm, q2, k2, v2, bt2, [P2], [C2], out2, None, ws2, s2), 5, 2, s2)
             fl = 4 * 64 * Hq2 * (C2 * P2 + C2 * (C2 + 1) // 2)
-            return {"workload": "fp32, 64/8 heads, head_dim 64, P=8192, C=8192", "flops": fl, "ms": round(ms, 3),
-                    "tflops": round(fl / (ms * 1e-3) / 1e12, 1), "peak": 157.3,
-                    "frac_fp32_mfma_peak": round(fl / (ms * 1e-3) / 1e12 / 157.3, 4)}
+            return {"workload": "fp32, 64/8 heads, head_dim 64, P=8192, C=8192", "flops": fl, "ms": round(us / 1e3, 3),
+                    "tflops": round(fl / (us * 1e-6) / 1e12, 1), "peak": 157.3,
+                    "frac_fp32_mfma_peak": round(fl / (us * 1e-6) / 1e12 / 157.3, 4)}
 
         result["attn_fp32"] = fp32_attention()
         torch.cuda.empty_cache()
         # a small chunk against a long prefix (16 new tokens behind 131056 cached ones, 64/8 heads): 8 work
         # items for 256 CUs unless the keys are split
-        result["attn_small_chunk"] = whole_vs_split(131056, 16, 64, 8, 20)
-        # just above one work item per compute unit (10240 new tokens, 8/1 heads: 320 items): the whole-row form
-        # runs a second, mostly empty round
-        result["attn_uneven_rounds"] = whole_vs_split(120832, 10240, 8, 1, 6)
+        result["attn_small_chunk"] = default_entry_forms(131056, 16, 64, 8, 20)
+        # just above one work item per compute unit (10240 new tokens, 8/1 heads: 320 items): whole rows run a
+        # second, mostly empty round
+        result["attn_uneven_rounds"] = default_entry_forms(120832, 10240, 8, 1, 6)
         torch.cuda.empty_cache()
         torch.cuda.synchronize()
-        ceil = mfma_ceiling()
-        if ceil is not None:
+        mf = probe("mfma")
+        if mf is not None:
             result["mfma_alone"] = {
-                "what": "back-to-back bf16 32x32x16 MFMAs, nothing else running, 2 waves per SIMD, ~15 ms per case: "
-                        "the board lowers its clock to hold its power limit, and MFMA power follows operand bit activity",
-                **ceil,
-                "attn_vs_random_data_rate": round(result["roofline"]["achieved"] / ceil["random"]["tflops"], 4)}
+                "what": "back-to-back bf16 MFMAs, nothing else running, 2 waves per SIMD: the board lowers its clock to hold "
+                        "its power limit, and MFMA power follows operand bit activity and tile shape (the attention "
+                        "kernel uses 16x16x32 tiles)", **mf,
+                "attn_vs_random_data_rate": round(result["roofline"]["achieved"] / mf["16x16x32"]["random"]["tflops"], 4)}
+        cp = probe("copy")
+        if cp is not None:
+            result["copy_ceiling"]["probes"] = {
+                "what": "bench_probes.hip: the pack's access pattern (2048 scattered 32 KiB pages for K and for V -> "
+                        "contiguous) as a copy, read only and write only; the copy at other sizes fitted to fixed cost "
+                        "per launch + bytes / steady-state rate", **cp,
+                "read_only_frac_hbm_peak": round(cp["read_only"]["GBs"] / HBM_PEAK_GBS, 4),
+                "write_only_frac_hbm_peak": round(cp["write_only"]["GBs"] / HBM_PEAK_GBS, 4),
+                "steady_state_frac_hbm_peak": round(cp["steady_state_GBs"] / HBM_PEAK_GBS, 4)}
+
     if args.cpu_rows > 0:
-        # the CPU oracle, as it stands, on a bounded sample of the same attention workload
+        # the CPU oracle, as it stands, on a bounded sample of the same workloads
         import oracle
-        case = W.make_config_attn(args.attn_config, poison=False) if args.attn_config != attn.idx else attn.case
+        case = W.make_config_attn(args.attn_config, poison=False)
         rng = np.random.default_rng(1)
         rq = rng.integers(0, case.batch, size=args.cpu_rows)
         rows = np.stack([rq, rng.integers(0, case.num_q_heads, size=args.cpu_rows),
@@ -576,6 +599,28 @@ def main():
                                   "sample": f"{rows.shape[0]} uniformly drawn (head, row) outputs of the same config-"
                                             f"{args.attn_config} tensors, fp64, {dt:.1f} s; "
                                             f"full tensor would take ~{case.flops() / (row_flops / dt):.0f} s"}
+        del case
+        # the copy leg: the oracle's per-page memcpy on a host copy of one configuration-5 layer
+        hrng = np.random.default_rng(sh["seed"])
+        kp = hrng.integers(0, 256, size=(N2, pb), dtype=np.uint8)
+        vp = hrng.integers(0, 256, size=(N2, pb), dtype=np.uint8)
+        cores = oracle.num_threads()
+        cpu_copy = {"unit": "GB/s", "kind": "oracle", "bytes_per_layer": copy_bytes,
+                    "sample": "one configuration-5 layer (2048 pages of 32 KiB, K and V) on host memory, best of 3 "
+                              "passes per leg; pack as the oracle's wrapper does it, output buffers allocated per call"}
+        for threads in sorted({1, cores}):
+            best_p, best_u = 1e30, 1e30
+            for _ in range(3):
+                t0 = time.perf_counter()
+                ko, vo = oracle.kv_pack_layer(kp, vp, dst_ids_host, threads=threads)
+                best_p = min(best_p, time.perf_counter() - t0)
+                t0 = time.perf_counter()
+                oracle.kv_unpack_layer(ko, vo, dst_ids_host, kp, vp, threads=threads)
+                best_u = min(best_u, time.perf_counter() - t0)
+            cpu_copy[f"threads_{threads}"] = {"pack_GBs": round(copy_bytes / best_p / 1e9, 2),
+                                              "unpack_GBs": round(copy_bytes / best_u / 1e9, 2)}
+        cpu_copy["cores"] = cores
+        result["cpu_baseline_copy"] = cpu_copy
     print(json.dumps(result))
 
 

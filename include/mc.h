@@ -103,7 +103,14 @@ size_t mc_prefill_attn_workspace_bytes(const mc_attn_params* p, int32_t batch,
  *   out          dev  [total_new_tokens, Hq, D]   dtype of q, every row written
  *   lse          dev  [total_new_tokens, Hq] fp32, or NULL
  *   workspace    dev  >= mc_prefill_attn_workspace_bytes(...), 16-byte aligned;
- *                     in use until the enqueued work has finished
+ *                     in use until the enqueued work has finished.  A workspace of at least
+ *                     mc_prefill_attn_auto_workspace_bytes(...) lets the call run over key slices
+ *                     + merge (as mc_prefill_attn_auto does) whenever whole rows would leave
+ *                     compute units idle: a small chunk behind a long prefix, or a number of work
+ *                     items just above a multiple of the 256 compute units.  The result is the
+ *                     same to the tolerance of the two forms, not bit for bit; callers that need
+ *                     one fixed form pass the minimal workspace (always whole rows) or call
+ *                     mc_prefill_attn_paged_split themselves.
  *
  * Token slots at or beyond P_r + C_r in a request's last page, and pages the
  * block tables do not name, are never read as values (they may hold NaN).

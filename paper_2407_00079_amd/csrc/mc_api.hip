@@ -226,6 +226,14 @@ mc_status mc_prefill_attn_paged(const mc_attn_params* p, const void* q, const vo
                                 const int32_t* block_tables, int32_t max_pages_per_req,
                                 const int32_t* prefix_lens, const int32_t* new_lens, int32_t batch, void* out,
                                 float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  // A launch that would leave compute units idle (a small chunk behind a long prefix, or a work-item count just
+  // above a multiple of the compute units) runs over key slices + merge when the caller's workspace has room
+  // for the partial results; with the minimal workspace it runs whole-row.
+  AutoLayout lay;
+  if (workspace != nullptr && batch > 0 && prefix_lens != nullptr && new_lens != nullptr &&
+      auto_layout(p, prefix_lens, new_lens, batch, &lay) && lay.kv_splits > 1 && workspace_bytes >= lay.total)
+    return mc_prefill_attn_auto(p, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens, batch,
+                                out, lse, workspace, workspace_bytes, hip_stream);
   return attn_enqueue(p, q, k_pool, v_pool, block_tables, max_pages_per_req, prefix_lens, new_lens, batch, out, lse,
                       0, nullptr, nullptr, workspace, workspace_bytes, hip_stream);
 }

@@ -207,3 +207,51 @@ def test_copies_replay_from_a_hip_graph(oracle):
         oracle.kv_unpack_layer(ref_k, ref_v, ids, want_k, want_v)
         np.testing.assert_array_equal(pool2_k.cpu().numpy(), want_k, err_msg=f"replay {rep}")
         np.testing.assert_array_equal(pool2_v.cpu().numpy(), want_v, err_msg=f"replay {rep}")
+
+
+def test_all_80_layers_of_the_streaming_configuration(oracle):
+    """Configuration 5 in full: for each of the 80 layers, the 2048 listed pages of a scattered source pool (K and V,
+    32 KiB pages) are packed into contiguous buffers and unpacked into a second pool under an independent permutation,
+    pack on one stream and unpack on another, ordered per layer by an event.  Every layer is compared with the oracle's
+    pack and unpack of the same bytes: the packed buffers, every listed page of the second pool, and that the pages
+    not listed kept their fill."""
+    sh = W.config_shapes(5)
+    L, n, pb, N1, N2 = sh["layers"], sh["n"], sh["page_bytes"], sh["num_pages"], sh["num_pages_dst"]
+    rng = np.random.default_rng(sh["seed"])
+    ids1 = rng.permutation(N1)[:n].astype(np.int32)
+    ids2 = rng.permutation(N2)[:n].astype(np.int32)
+    d_ids1, d_ids2 = _dev(ids1), _dev(ids2)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(sh["seed"])
+    FILL = 0xA5
+    k1 = torch.randint(0, 256, (L, N1, pb), dtype=torch.uint8, device="cuda:0", generator=gen)     # 10 GiB
+    v1 = torch.randint(0, 256, (L, N1, pb), dtype=torch.uint8, device="cuda:0", generator=gen)
+    k2 = torch.full((L, N2, pb), FILL, dtype=torch.uint8, device="cuda:0")
+    v2 = torch.full((L, N2, pb), FILL, dtype=torch.uint8, device="cuda:0")
+    k_lin = torch.zeros((L, n, pb), dtype=torch.uint8, device="cuda:0")                             # 5 GiB
+    v_lin = torch.zeros((L, n, pb), dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    st_pack, st_unpack = torch.cuda.Stream(), torch.cuda.Stream()
+    for l in range(L):
+        B.mc_kv_pack_layer(k1[l], v1[l], N1, pb, d_ids1, n, k_lin[l], v_lin[l], st_pack)
+        packed = torch.cuda.Event()
+        packed.record(st_pack)
+        st_unpack.wait_event(packed)
+        B.mc_kv_unpack_layer(k_lin[l], v_lin[l], N2, pb, d_ids2, n, k2[l], v2[l], st_unpack)
+    torch.cuda.synchronize()
+    print("all 80 layers packed and unpacked; comparing with the oracle layer by layer", flush=True)
+    host = [torch.empty((N1, pb), dtype=torch.uint8, pin_memory=True) for _ in range(2)]
+    host2 = [torch.empty((N2, pb), dtype=torch.uint8, pin_memory=True) for _ in range(2)]
+    lin = [torch.empty((n, pb), dtype=torch.uint8, pin_memory=True) for _ in range(2)]
+    for l in range(L):
+        for h, src in zip(host + host2 + lin, (k1[l], v1[l], k2[l], v2[l], k_lin[l], v_lin[l])):
+            h.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        k_ref, v_ref = oracle.kv_pack_layer(host[0].numpy(), host[1].numpy(), ids1, threads=4)
+        assert np.array_equal(lin[0].numpy(), k_ref) and np.array_equal(lin[1].numpy(), v_ref), f"packed buffers, layer {l}"
+        k2_ref = np.full((N2, pb), FILL, dtype=np.uint8)
+        v2_ref = np.full((N2, pb), FILL, dtype=np.uint8)
+        oracle.kv_unpack_layer(k_ref, v_ref, ids2, k2_ref, v2_ref, threads=4)
+        assert np.array_equal(host2[0].numpy(), k2_ref) and np.array_equal(host2[1].numpy(), v2_ref), f"second pool, layer {l}"
+        if l % 16 == 15:
+            print(f"layers 0..{l} equal the oracle", flush=True)

@@ -121,6 +121,33 @@ def test_automatic_form_matches_oracle(oracle, prefix, new):
                                ws[:need - 1] if splits > 1 else ws[:8])
 
 
+def test_default_entry_takes_key_slices_when_the_workspace_has_room(oracle):
+    # mc_prefill_attn_paged with the larger workspace is the automatic form (bit for bit); with the minimal one it
+    # is the whole-row form; both are the oracle's result
+    prefix, new = [4000], [16]
+    case = W.make_attn_case(66, W.BF16, 16, 2, 128, 16, prefix, new, 300)
+    dc = DeviceCase(case)
+    assert B.mc_prefill_attn_suggest_kv_splits(dc.params, prefix, new) > 1
+    need = B.mc_prefill_attn_auto_workspace_bytes(dc.params, prefix, new)
+    assert need > B.mc_prefill_attn_workspace_bytes(dc.params, 1, 16)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    B.mc_prefill_attn_auto(dc.params, dc.q, dc.k_pool, dc.v_pool, dc.block_tables, prefix, new, dc.out, dc.lse, ws)
+    torch.cuda.synchronize()
+    auto_o, auto_l = dc.out.clone(), dc.lse.clone()
+    dc.out.fill_(float("nan"))
+    dc.lse.fill_(float("nan"))
+    B.mc_prefill_attn_paged(dc.params, dc.q, dc.k_pool, dc.v_pool, dc.block_tables, prefix, new, dc.out, dc.lse, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dc.out, auto_o) and torch.equal(dc.lse, auto_l)
+    dc.run()                                                     # minimal workspace: whole rows
+    out, lse = dc.result()
+    ref_out, ref_lse, _ = oracle.case_full(case)
+    check_close(out, ref_out, W.BF16, "whole-row form")
+    check_close(auto_o.float().cpu().numpy().astype(np.float64), ref_out, W.BF16, "key slices through the default entry")
+    assert np.abs(lse - ref_lse).max() <= TOL[W.BF16]["lse_abs"]
+    assert np.abs(auto_l.cpu().numpy() - ref_lse).max() <= TOL[W.BF16]["lse_abs"]
+
+
 def test_merge_of_foreign_partials(oracle):
     # partials that did not come from this library's kernel: -inf parts, NaN payload behind them, all-empty rows
     rng = np.random.default_rng(8)
