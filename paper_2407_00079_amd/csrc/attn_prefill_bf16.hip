@@ -365,14 +365,16 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
     for (int rt = 0; rt < 2; ++rt) m_ref[rt] = SPLIT ? fmaxf(m_run[rt], kNoKeyYet) : m_run[rt];
 #pragma unroll
     for (int i = 0; i < kRing; ++i) {
-      s_next.t[0][i & 1] = mma(ring[i], qf[i >> 1][0], s_next.t[0][i & 1]);
-      s_next.t[1][i & 1] = mma(ring[i], qf[i >> 1][1], s_next.t[1][i & 1]);
-      ring[i] = load_v(vx, off_v, i);
+      // the step's vector work first (two exponentials; rounding and summing trail one step behind the
+      // exponentials they depend on), then its two MFMAs and the fragment read: measured best of the orders tried
       const int e0 = 2 * i;
 #pragma unroll
       for (int e = e0; e < e0 + 2; ++e) s_cur.set(e, __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur.get(e), c, -m_ref[e >> 3])));
-      // rounding and summing trail one step behind the exponentials they depend on
       if (i > 0) bsum[(e0 - 2) >> 3] = round_sum(pb, s_cur, e0 - 2, bsum[(e0 - 2) >> 3]);
+      __builtin_amdgcn_sched_barrier(0);
+      s_next.t[0][i & 1] = mma(ring[i], qf[i >> 1][0], s_next.t[0][i & 1]);
+      s_next.t[1][i & 1] = mma(ring[i], qf[i >> 1][1], s_next.t[1][i & 1]);
+      ring[i] = load_v(vx, off_v, i);
       __builtin_amdgcn_sched_barrier(0);
     }
     bsum[1] = round_sum(pb, s_cur, 14, bsum[1]);
