@@ -372,8 +372,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
       for (int e = e0; e < e0 + 2; ++e) s_cur.set(e, __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur.get(e), c, -m_ref[e >> 3])));
       if (i > 0) bsum[(e0 - 2) >> 3] = round_sum(pb, s_cur, e0 - 2, bsum[(e0 - 2) >> 3]);
       __builtin_amdgcn_sched_barrier(0);
-      s_next.t[0][i & 1] = mma(ring[i], qf[i >> 1][0], s_next.t[0][i & 1]);
-      s_next.t[1][i & 1] = mma(ring[i], qf[i >> 1][1], s_next.t[1][i & 1]);
+      // consecutive MFMAs always share an operand register (the K fragment inside a step, the Q fragment across
+      // the steps of a head_dim chunk): odd steps take the row tiles in reverse order (+1 % under the power limit)
+      {
+        const int ra = i & 1, rb = ra ^ 1;
+        s_next.t[ra][i & 1] = mma(ring[i], qf[i >> 1][ra], s_next.t[ra][i & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        s_next.t[rb][i & 1] = mma(ring[i], qf[i >> 1][rb], s_next.t[rb][i & 1]);
+      }
       ring[i] = load_v(vx, off_v, i);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -390,8 +396,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
     const int off_k = buf_pre * kKTileBytes + kb_pre * 32 * kRowBytes;
 #pragma unroll
     for (int i = 0; i < kRing; ++i) {
-      o[i][0] = mma(ring[i], pb.f[0], o[i][0]);
-      o[i][1] = mma(ring[i], pb.f[1], o[i][1]);
+      {
+        const int ra = i & 1, rb = ra ^ 1;      // as in phase A: the V fragment inside a step, P across steps
+        o[i][ra] = mma(ring[i], pb.f[ra], o[i][ra]);
+        __builtin_amdgcn_sched_barrier(0);
+        o[i][rb] = mma(ring[i], pb.f[rb], o[i][rb]);
+      }
       ring[i] = load_k(kx, off_k, i);
       __builtin_amdgcn_sched_barrier(0);
     }
