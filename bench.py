@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--layers", type=int, default=8, help="distinct per-layer pools the steps cycle through")
     ap.add_argument("--cpu-rows", type=int, default=8192, help="rows the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--no-extra", action="store_true", help="only the headline step")
+    ap.add_argument("--copies-only", action="store_true",
+                    help="only the isolated pack / unpack loops (80 launches back to back each), for profiling them alone")
     ap.add_argument("--zero-inputs", action="store_true",
                     help="DIAGNOSTIC, not a measurement of the workload: Q, K and V all zero (same kernels, same "
                          "instruction stream, no operand bit activity) to show what the board's power limit costs")
@@ -273,6 +275,47 @@ def main():
             "source": "committed rocprofv3 counter summary profiles/hbm_traffic_bench_step.txt (FETCH_SIZE / WRITE_SIZE "
                       "calibrated on a plain copy), not counted in this run"}
 
+    def isolated_copies(result, s):
+        def pack_ordered(l, stream):
+            B.mc_kv_pack_layer_ordered(k_pool[l], v_pool[l], N2, pb, dst_ids, order, n, k_store[l], v_store[l], stream)
+
+        # pack writes its output in list order, unpack (with the order) its pool pages in address order; the other
+        # two combinations are measured for comparison: the write side is the one that wants to be sequential
+        for name, fn in (("pack", pack), ("unpack", unpack), ("pack_pool_order", pack_ordered),
+                         ("unpack_list_order", unpack_list_order)):
+            it = iter(range(10 ** 9))
+            us = timed_loop(lambda: fn(next(it) % LAY, s), 80, LAY, s)      # 80 layers back to back, launch gaps included
+            gbs = copy_bytes / (us * 1e-6) / 1e9
+            result[f"roofline_{name}"] = {"kernel": f"kv_copy_kernel<{name.split('_')[0]}>", "bound": "hbm", "achieved": round(gbs, 1),
+                                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                                          "us_per_layer": round(us, 2), "bytes_per_launch": copy_bytes,
+                                          "traffic": hbm(name.split("_")[0])}
+        # what a copy of the same bytes reaches on this board with nothing scattered: the same kernel with the pages
+        # in pool order (ids 0 .. n-1), the runtime's device-to-device copy, and the stand-alone probes: the read-only
+        # and write-only halves of the access pattern, fixed cost per launch and steady-state rate
+        seq_ids = torch.arange(n, dtype=torch.int32, device=dev)
+
+        def pack_contiguous(l, stream):
+            B.mc_kv_pack_layer(k_pool[l], v_pool[l], N2, pb, seq_ids, n, k_store[l], v_store[l], stream)
+
+        def runtime_copy(l, stream):
+            k_store[l].copy_(k_pool[l, :n])
+            v_store[l].copy_(v_pool[l, :n])
+
+        ceiling = {}
+        for name, fn in (("same_kernel_contiguous", pack_contiguous), ("runtime_d2d_copy", runtime_copy)):
+            it = iter(range(10 ** 9))
+            us = timed_loop(lambda: fn(next(it) % LAY, s), 80, LAY, s)
+            ceiling[name] = {"GBs": round(copy_bytes / (us * 1e-6) / 1e9, 1), "us_per_layer": round(us, 2),
+                             "frac_hbm_peak": round(copy_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+        result["copy_ceiling"] = {"what": "the same 2 x 64 MiB read and written with no scatter at all", **ceiling}
+
+    if args.copies_only:
+        result = {"what": "isolated pack / unpack loops only (bench.py --copies-only)"}
+        isolated_copies(result, torch.cuda.current_stream())
+        print(json.dumps(result))
+        return
+
     def attn_roofline(attn, attn_ms):
         avg = sum(attn_ms) / len(attn_ms)
         tf = attn.flops / (avg * 1e-3) / 1e12
@@ -314,39 +357,7 @@ def main():
         result["attn_one_shot_call"] = {"ms_per_call_back_to_back": round(us / 1e3, 4),
                                         "what": "mc_prefill_attn_paged: prepare + run in one call"}
 
-        def pack_ordered(l, stream):
-            B.mc_kv_pack_layer_ordered(k_pool[l], v_pool[l], N2, pb, dst_ids, order, n, k_store[l], v_store[l], stream)
-
-        # pack writes its output in list order, unpack (with the order) its pool pages in address order; the other
-        # two combinations are measured for comparison: the write side is the one that wants to be sequential
-        for name, fn in (("pack", pack), ("unpack", unpack), ("pack_pool_order", pack_ordered),
-                         ("unpack_list_order", unpack_list_order)):
-            it = iter(range(10 ** 9))
-            us = timed_loop(lambda: fn(next(it) % LAY, s), 80, LAY, s)      # 80 layers back to back, launch gaps included
-            gbs = copy_bytes / (us * 1e-6) / 1e9
-            result[f"roofline_{name}"] = {"kernel": f"kv_copy_kernel<{name.split('_')[0]}>", "bound": "hbm", "achieved": round(gbs, 1),
-                                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
-                                          "us_per_layer": round(us, 2), "bytes_per_launch": copy_bytes,
-                                          "traffic": hbm(name.split("_")[0])}
-        # what a copy of the same bytes reaches on this board with nothing scattered: the same kernel with the pages
-        # in pool order (ids 0 .. n-1), the runtime's device-to-device copy, and the stand-alone probes: the read-only
-        # and write-only halves of the access pattern, fixed cost per launch and steady-state rate
-        seq_ids = torch.arange(n, dtype=torch.int32, device=dev)
-
-        def pack_contiguous(l, stream):
-            B.mc_kv_pack_layer(k_pool[l], v_pool[l], N2, pb, seq_ids, n, k_store[l], v_store[l], stream)
-
-        def runtime_copy(l, stream):
-            k_store[l].copy_(k_pool[l, :n])
-            v_store[l].copy_(v_pool[l, :n])
-
-        ceiling = {}
-        for name, fn in (("same_kernel_contiguous", pack_contiguous), ("runtime_d2d_copy", runtime_copy)):
-            it = iter(range(10 ** 9))
-            us = timed_loop(lambda: fn(next(it) % LAY, s), 80, LAY, s)
-            ceiling[name] = {"GBs": round(copy_bytes / (us * 1e-6) / 1e9, 1), "us_per_layer": round(us, 2),
-                             "frac_hbm_peak": round(copy_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
-        result["copy_ceiling"] = {"what": "the same 2 x 64 MiB read and written with no scatter at all", **ceiling}
+        isolated_copies(result, s)
         # append of the step's chunk alone, launched back to back
         c = attn.case
         us = timed_loop(lambda: attn.append(s), 80, 5, s)
