@@ -8,8 +8,8 @@
  *
  * What it computes (paper Section 3, steps 1-2: a prefill node receives the
  * ids of reusable prefix blocks plus the ids of all blocks of the request and
- * finishes prefill "using the prefix cache"; Section 5.2: per-layer load and
- * store of KVCache around attention):
+ * finishes prefill for the rest on top of the cached prefix; Section 5.2:
+ * per-layer load and store of KVCache around attention):
  *
  *   request r has P_r reused prefix tokens and C_r new tokens; chunk row i is
  *   absolute position P_r + i and sees keys j = 0 .. P_r + i (itself included);
@@ -236,7 +236,7 @@ int mco_kv_unpack_layer(const uint8_t* k_in, const uint8_t* v_in, int64_t num_pa
 }
 
 /*
- * Incremental prefill "stores the newly generated incremental KVCache" (Section 3, step 2):
+ * Incremental prefill keeps the KVCache of the tokens it has just computed (Section 3, step 2):
  * token i of request r (absolute position P_r + i) goes to slot (P_r + i) % S of page
  * block_table[r][(P_r + i) / S], for every KV head, bytes verbatim.  k_new / v_new are
  * [total_new, Hkv, row_bytes], pools are [N, Hkv, S, row_bytes].  Slots not written keep
