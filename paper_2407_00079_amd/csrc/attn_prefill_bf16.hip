@@ -19,9 +19,14 @@
 //     the 4 lane groups, which the steady state needs only at the very end.
 //   * Per 32-key block: 16 score MFMAs (2 key tiles x 2 row tiles x 4 head_dim steps of 32) and
 //     16 P V MFMAs (8 head_dim tiles x 2 row tiles), 8 K fragments and 8 V fragments from LDS.
-//   * K/V tiles, their copy into LDS, the page walk, the lazy softmax reference with its sum
-//     guard, the two-phase ring schedule and the half-step skew of the two waves of a SIMD are
-//     those of attn_prefill.hip; the swizzles differ (fragment shapes differ).
+//   * K/V tiles, their copy into LDS, the page walk, the lazy softmax reference, the two-phase
+//     ring schedule and the half-step skew of the two waves of a SIMD are those of
+//     attn_prefill.hip; the swizzles differ (fragment shapes differ).
+//   * Vector instructions are what the matrix pipe does not hide here (each one costs its issue
+//     time, measured by removing them one kind at a time), so the softmax keeps only what it
+//     cannot do without: per score one fma and one exp2, per pair one rounding to bf16.  The row
+//     sums of the rounded probabilities come from two more MFMAs per block (ones x P^T), and the
+//     guard of the lazy reference is an OR over the packed probabilities (see kRefLift).
 #include <type_traits>
 
 #include "attn_device.h"
@@ -37,6 +42,14 @@ constexpr int kD = 128;
 constexpr int kSteps = kD / 32;       // contraction steps of the scores over head_dim
 constexpr int kDTiles = kD / 16;      // 16-column tiles of the output
 constexpr int kRing = 8;              // K fragments of a block = V fragments of a block
+// The reference of a row's probabilities is kept kRefLift (log2 units) ABOVE the largest score it was last set
+// from, so probabilities are at most 2^-7 then and stay below 2 while later scores outgrow that maximum by less
+// than 8: "some probability reached 2" is bit 14 of a bf16 pattern, which an OR over the block's packed
+// probabilities finds (bit 14 is also set in inf and NaN).  The reference is raised when a score comes within
+// kRaiseAbove of making its probability 2, which is before the guard can fire.
+constexpr float kRefLift = 7.0f;
+constexpr float kRaiseAbove = 0.5f;
+constexpr uint32_t kGuardBits = 0x40004000u;
 static_assert(kRing == 2 * kSteps && kRing == kDTiles, "both phases walk the ring once");
 
 __device__ __forceinline__ acc4 mma(frag a, frag b, acc4 c) {
@@ -103,21 +116,21 @@ struct Scores {
       for (int kt = 0; kt < 2; ++kt) t[rt][kt] = acc4{0.f, 0.f, 0.f, 0.f};
   }
 };
-// a block's probabilities as P V multiplies them: per row tile, the B operand of the 32-key step
+// a block's probabilities as P V multiplies them: per row tile, the B operand of the 32-key step, kept as four
+// words of two bf16 each (word k = keys 2 k, 2 k + 1 of the lane's eight)
 struct PBlock {
-  frag f[2];
+  u32x4 w[2];
+  __device__ __forceinline__ frag f(int rt) const { return __builtin_bit_cast(frag, w[rt]); }
 };
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 
-// round probabilities e, e + 1 (same row tile) into their fragment and add the ROUNDED values to acc
-__device__ __forceinline__ float round_sum(PBlock& b, const Scores& p, int e, float acc) {
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-  const bf16x2 pr = {(__bf16)p.get(e), (__bf16)p.get(e + 1)};
-  b.f[e >> 3][e & 7] = pr[0];
-  b.f[e >> 3][(e & 7) + 1] = pr[1];
-  return __builtin_amdgcn_fdot2_f32_bf16(pr, ones, acc, false);
+// round probabilities e, e + 1 (same row tile) into their fragment
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void round_pair(PBlock& b, const Scores& p, int e) {
+  const f32x2 pp = {p.get(e), p.get(e + 1)};
+  const bf16x2 pr = __builtin_convertvector(pp, bf16x2);      // one v_cvt_pk_bf16_f32 (round to nearest even)
+  b.w[e >> 3][(e & 7) >> 1] = __builtin_bit_cast(uint32_t, pr);
 }
-
 template <int WAVES, bool SPLIT>
 __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) char smem[kBuffers * (kKTileBytes + kVTileBytes)];
@@ -253,7 +266,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
   // ---- running softmax state and output accumulators: o[dt][rt] register r = column 16 dt + 4 g + r of row 16 rt + j
   acc4 o[kDTiles][2];
   float m_run[2] = {-INFINITY, -INFINITY};   // reference of the probabilities accumulated so far (log2 units)
-  float l_sum[2] = {0.f, 0.f};               // this lane's share of the row sums (groups merged at the end)
+  // Row sums come from the matrix cores: l_acc[rt] += ones (16 x 32) . P^T (32 keys x 16 rows) leaves, in all four
+  // registers of lane (j, g), the sum of row j's rounded probabilities over the whole block, lane groups included
+  // (2 MFMAs per block instead of 8 dot-product instructions, which cost a matrix-pipe slot each).
+  acc4 l_acc[2] = {acc4{0.f, 0.f, 0.f, 0.f}, acc4{0.f, 0.f, 0.f, 0.f}};
+  frag ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+  asm volatile("" : "+v"(ones));             // kept in registers, not rebuilt at every use
 #pragma unroll
   for (int dt = 0; dt < kDTiles; ++dt)
 #pragma unroll
@@ -299,40 +319,41 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
       for (int e = 1; e < 8; ++e) m = fmaxf(m, s.t[rt][e >> 2][e & 3]);
       mx[rt] = max_over_groups(m) * c;
     }
-    if (__builtin_amdgcn_ballot_w64(mx[0] > m_run[0] + kRescaleSlack || mx[1] > m_run[1] + kRescaleSlack) != 0) {
+    if (__builtin_amdgcn_ballot_w64(mx[0] > m_run[0] + kRaiseAbove || mx[1] > m_run[1] + kRaiseAbove) != 0) {
 #pragma unroll
       for (int rt = 0; rt < 2; ++rt) {
-        const float m_new = fmaxf(m_run[rt], mx[rt]);
+        const float m_new = fmaxf(m_run[rt], mx[rt] + kRefLift);
         // a row that has seen no key yet keeps -inf (only in a slice that starts beyond the row's diagonal)
         const float alpha = (SPLIT && m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m_run[rt] - m_new);
-        l_sum[rt] *= alpha;
+        l_acc[rt] *= alpha;
         m_run[rt] = m_new;
 #pragma unroll
         for (int dt = 0; dt < kDTiles; ++dt) o[dt][rt] *= alpha;
       }
     }
   };
-  // scores -> probabilities against the references as they stand, rounded the way P V multiplies them;
-  // adds this lane's share of the block's row sums to bsum
-  auto probabilities = [&](Scores& s, PBlock& pb, float (&bsum)[2]) __attribute__((always_inline)) {
+  // scores -> probabilities against the references as they stand, rounded the way P V multiplies them
+  auto probabilities = [&](Scores& s, PBlock& pb) __attribute__((always_inline)) {
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) {
       const float m_ref = SPLIT ? fmaxf(m_run[rt], kNoKeyYet) : m_run[rt];
 #pragma unroll
       for (int e = 8 * rt; e < 8 * rt + 8; ++e) s.set(e, __builtin_amdgcn_exp2f(__builtin_fmaf(s.get(e), c, -m_ref)));
-      float acc = 0.f;
 #pragma unroll
-      for (int e = 8 * rt; e < 8 * rt + 8; e += 2) acc = round_sum(pb, s, e, acc);
-      bsum[rt] = acc;
+      for (int e = 8 * rt; e < 8 * rt + 8; e += 2) round_pair(pb, s, e);
     }
+  };
+  auto add_row_sums = [&](const PBlock& pb) __attribute__((always_inline)) {
+    l_acc[0] = mma(ones, pb.f(0), l_acc[0]);
+    l_acc[1] = mma(ones, pb.f(1), l_acc[1]);
   };
   auto pv_block = [&](int buf, int kb, const PBlock& pb) __attribute__((always_inline)) {
     const int off = buf * kVTileBytes + kb * 32 * kRowBytes;
 #pragma unroll
     for (int dt = 0; dt < kDTiles; ++dt) {
       const frag vf = load_v(vx, off, dt);
-      o[dt][0] = mma(vf, pb.f[0], o[dt][0]);
-      o[dt][1] = mma(vf, pb.f[1], o[dt][1]);
+      o[dt][0] = mma(vf, pb.f(0), o[dt][0]);
+      o[dt][1] = mma(vf, pb.f(1), o[dt][1]);
     }
   };
 
@@ -351,16 +372,15 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
 #pragma unroll
     for (int i = 0; i < kRing; ++i) ring[i] = load_k(kx, off, i);
   };
-  // a lane's sum of 8 probabilities above this (or not finite) means some score outgrew the reference by
-  // more than the slack: the block is then recomputed against its true maxima (nothing was accumulated yet)
-  constexpr float kSumGuard = 2048.0f;   // 8 probabilities of at most 2^kRescaleSlack each
+  // a probability of 2 or more (or not finite) means its score outgrew the reference: the block is then
+  // recomputed against its true maxima (nothing was accumulated yet)
   PBlock pb;
   auto phase_a = [&](int buf_cur, int kb_cur) __attribute__((always_inline)) {
     const int off_v = buf_cur * kVTileBytes + kb_cur * 32 * kRowBytes;
     s_cur = s_next;
     s_next.zero();
-    float bsum[2] = {0.f, 0.f};
     float m_ref[2];
+    uint32_t seen = 0;          // OR of the block's packed probabilities
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) m_ref[rt] = SPLIT ? fmaxf(m_run[rt], kNoKeyYet) : m_run[rt];
 #pragma unroll
@@ -370,7 +390,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
       const int e0 = 2 * i;
 #pragma unroll
       for (int e = e0; e < e0 + 2; ++e) s_cur.set(e, __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur.get(e), c, -m_ref[e >> 3])));
-      if (i > 0) bsum[(e0 - 2) >> 3] = round_sum(pb, s_cur, e0 - 2, bsum[(e0 - 2) >> 3]);
+      if (i > 0) round_pair(pb, s_cur, e0 - 2);
+      // the guard's OR trails the rounding by another step
+      if (i == 3) seen = pb.w[0][0] | pb.w[0][1];
+      if (i == 5) seen |= pb.w[0][2] | pb.w[0][3];
+      if (i == 7) seen |= pb.w[1][0] | pb.w[1][1];
       __builtin_amdgcn_sched_barrier(0);
       // consecutive MFMAs always share an operand register (the K fragment inside a step, the Q fragment across
       // the steps of a head_dim chunk): odd steps take the row tiles in reverse order (+1 % under the power limit)
@@ -383,14 +407,13 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
       ring[i] = load_v(vx, off_v, i);
       __builtin_amdgcn_sched_barrier(0);
     }
-    bsum[1] = round_sum(pb, s_cur, 14, bsum[1]);
-    if (__builtin_amdgcn_ballot_w64(!(bsum[0] <= kSumGuard) || !(bsum[1] <= kSumGuard)) != 0) {
+    round_pair(pb, s_cur, 14);
+    seen |= pb.w[1][2] | pb.w[1][3];
+    if (__builtin_amdgcn_ballot_w64((seen & kGuardBits) != 0) != 0) {
       qk_block(buf_cur, kb_cur, s_cur);
       settle_reference(s_cur, 0, std::false_type{});
-      probabilities(s_cur, pb, bsum);
+      probabilities(s_cur, pb);
     }
-    l_sum[0] += bsum[0];
-    l_sum[1] += bsum[1];
   };
   auto phase_b = [&](int buf_pre, int kb_pre) __attribute__((always_inline)) {
     const int off_k = buf_pre * kKTileBytes + kb_pre * 32 * kRowBytes;
@@ -398,9 +421,13 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
     for (int i = 0; i < kRing; ++i) {
       {
         const int ra = i & 1, rb = ra ^ 1;      // as in phase A: the V fragment inside a step, P across steps
-        o[i][ra] = mma(ring[i], pb.f[ra], o[i][ra]);
+        o[i][ra] = mma(ring[i], pb.f(ra), o[i][ra]);
         __builtin_amdgcn_sched_barrier(0);
-        o[i][rb] = mma(ring[i], pb.f[rb], o[i][rb]);
+        if (i == 0 || i == 1) {              // the row sums of the tile just used: the P operand stays where it is
+          l_acc[ra] = mma(ones, pb.f(ra), l_acc[ra]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        o[i][rb] = mma(ring[i], pb.f(rb), o[i][rb]);
       }
       ring[i] = load_k(kx, off_k, i);
       __builtin_amdgcn_sched_barrier(0);
@@ -411,10 +438,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
     if (!have_scores) qk_block(buf, kb, s);
     settle_reference(s, key0, std::true_type{});
     PBlock pbl;
-    float bsum[2];
-    probabilities(s, pbl, bsum);
-    l_sum[0] += bsum[0];
-    l_sum[1] += bsum[1];
+    probabilities(s, pbl);
+    add_row_sums(pbl);
     pv_block(buf, kb, pbl);
   };
 
@@ -483,7 +508,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
   // ---- epilogue: normalise, round, store; a lane holds 4 consecutive columns per (dt, rt)
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt) {
-    const float l_run = sum_over_groups(l_sum[rt]);
+    const float l_run = l_acc[rt][0];
     if (!live[rt]) continue;
     if (!SPLIT) {
       const float inv = 1.0f / l_run;
