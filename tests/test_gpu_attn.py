@@ -126,6 +126,28 @@ def test_large_scores(oracle):
     run_full(oracle, case, what="q x30")
 
 
+def test_scores_that_keep_outgrowing_the_reference(oracle):
+    """Scores that rise along the keys at eight different rates, one per head (from 0.3 to 20 log2 units per 32-key
+    block): the lazy softmax reference is outgrown by just under and just over its margin again and again, in the
+    pipelined tiles (long prefix) and in the diagonal ones."""
+    Hq, Hkv, D, S, P, C = 8, 1, 128, 16, 2000, 150
+    L = P + C
+    rng = np.random.default_rng(11)
+    u = rng.standard_normal(D)
+    u /= np.linalg.norm(u)
+    rates = np.array([0.3, 3.0, 6.9, 7.4, 7.9, 8.1, 12.0, 20.0])               # log2 units per 32 keys
+    ramp = (np.arange(L) / 32.0)[:, None, None]                                # blocks from key 0
+    k = (ramp * u[None, None, :] + 0.05 * rng.standard_normal((L, Hkv, D))).astype(np.float32)
+    v = rng.standard_normal((L, Hkv, D)).astype(np.float32)
+    scale_log2e = np.log2(np.e) / np.sqrt(D)
+    q = np.empty((C, Hq, D), np.float32)
+    for h in range(Hq):
+        q[:, h] = (rates[h] / scale_log2e) * u[None, :] + 0.05 * rng.standard_normal((C, D))
+    case = W.make_attn_case(12, W.BF16, Hq, Hkv, D, S, [P], [C], 256,
+                            logical=(W.f32_to_bf16_bits(q), [W.f32_to_bf16_bits(k)], [W.f32_to_bf16_bits(v)]))
+    run_full(oracle, case, what="rising scores")
+
+
 def test_outputs_do_not_depend_on_poison(oracle):
     case = W.make_attn_case(61, W.BF16, 8, 1, 128, 16, [37], [30], 32, keep_logical=True)
     clean = W.make_attn_case(61, W.BF16, 8, 1, 128, 16, [37], [30], 32, poison=False,
