@@ -25,9 +25,10 @@
 //   * Online softmax in fp32, base 2 (scale * log2 e folded into one fma).  Any
 //     reference below overflow gives the same quotient O / l, so fully visible
 //     blocks take no maxima at all: probabilities are formed against the reference
-//     as it stands, and a block whose probability sums show that a score outgrew it
-//     by more than 2^8 is recomputed against its true maximum (rare; O is rescaled
-//     only then).  Blocks on the chunk's diagonal take the masked, max-first path.
+//     as it stands, and a block whose probabilities show that a score outgrew it
+//     by more than 2^8 (fp32: by their sums; bf16: by a bit test on the rounded values)
+//     is recomputed against its true maximum (rare; O is rescaled only then).  Blocks
+//     on the chunk's diagonal take the masked, max-first path.
 //   * Two waves per SIMD, half a step apart: while one wave's softmax occupies the
 //     vector ALU under its score MFMAs, the other wave's P V MFMAs keep the matrix
 //     pipe busy.  Waves of the second half whose rows lie past the chunk's end exit
