@@ -63,7 +63,7 @@ typedef enum { MC_DTYPE_BF16 = 0, MC_DTYPE_F32 = 1 } mc_dtype;
 typedef struct {
   int32_t num_q_heads;  /* Hq */
   int32_t num_kv_heads; /* Hkv, divides Hq; query head h reads KV head h / (Hq / Hkv) */
-  int32_t head_dim;     /* D: 128 for bf16, 64 for f32 (one row = 256 bytes) */
+  int32_t head_dim;     /* D: 128 or 64 for bf16, 64 for f32 (one row = 256 or 128 bytes) */
   int32_t page_size;    /* S tokens per page: 16 */
   int64_t num_pages;    /* N pages in each pool */
   int32_t dtype;        /* mc_dtype of Q, K, V and O */
@@ -297,7 +297,7 @@ mc_status mc_prefill_attn_plan(const mc_attn_params* p, const int32_t* prefix_le
  *   lse        dev  [rows] fp32, or NULL
  *
  * A row whose parts are all -inf gives out = 0, lse = -inf.  (head_dim, dtype) must be
- * (128, MC_DTYPE_BF16) or (64, MC_DTYPE_F32).  rows == 0 is MC_OK and enqueues nothing.
+ * (128, MC_DTYPE_BF16), (64, MC_DTYPE_BF16) or (64, MC_DTYPE_F32).  rows == 0 is MC_OK and enqueues nothing.
  */
 mc_status mc_attn_merge_lse(const float* o_parts, const float* lse_parts, int32_t kv_splits, int64_t rows,
                             int32_t head_dim, int32_t dtype, void* out, float* lse, void* hip_stream);

@@ -208,6 +208,7 @@ extern "C" mc_status mc_prefill_attn_paged_noalloc(const mc_attn_params* p, cons
   args.Hkv = p->num_kv_heads;
   args.G = G;
   args.max_pages = max_pages_per_req;
+  args.head_dim = p->head_dim;
   args.scale_log2e = attn_scale_log2e(p);
   args.n_items = (int32_t)n_items;
   args.kv_splits = 0;

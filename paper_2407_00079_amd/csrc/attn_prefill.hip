@@ -45,8 +45,10 @@ namespace {
 // dtype traits: how fragments are fetched and multiplied
 // ---------------------------------------------------------------------------
 // bf16 rows as the merge kernel writes them (the bf16 attention kernel itself lives in attn_prefill_bf16.hip)
+template <int D>
 struct Bf16 {
-  static constexpr int kD = 128;
+  static constexpr int kD = D;
+  static constexpr int kOutRowBytes = D * 2;
   // four consecutive output columns
   static __device__ __forceinline__ void store4(char* orow, int col, float a, float b, float c, float d) {
     bf16x4 v;
@@ -60,6 +62,7 @@ struct Bf16 {
 
 struct F32 {
   static constexpr int kD = 64;
+  static constexpr int kOutRowBytes = kD * 4;
   static constexpr int kQKSteps = kD / 2;     // mfma 32x32x2 steps over head_dim
   static constexpr int kPVSteps = 16;         // one accumulator register (2 keys across halves) per step
   static constexpr int kDBlocks = kD / 32;
@@ -594,7 +597,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
   }
   if (!live) return;
   if (m != -INFINITY) acc *= 1.0f / z;
-  T::store4(reinterpret_cast<char*>(out) + row * kRowBytes, col, acc[0], acc[1], acc[2], acc[3]);
+  T::store4(reinterpret_cast<char*>(out) + row * T::kOutRowBytes, col, acc[0], acc[1], acc[2], acc[3]);
   if (lse != nullptr && col == 0) lse[row] = m != -INFINITY ? m + __logf(z) : -INFINITY;
 }
 
@@ -617,16 +620,21 @@ static void enqueue_merge(const float* o_parts, const float* lse_parts, int kv_s
                                                                                    rows, out, lse);
 }
 
-hipError_t launch_attn_merge(int dtype, const float* o_parts, const float* lse_parts, int kv_splits, int64_t rows,
-                             void* out, float* lse, hipStream_t stream) {
+hipError_t launch_attn_merge(int dtype, int head_dim, const float* o_parts, const float* lse_parts, int kv_splits,
+                             int64_t rows, void* out, float* lse, hipStream_t stream) {
   (void)hipGetLastError();
   const bool wide = kv_splits >= 8;   // enough parts to give each of 8 split lanes one
-  if (dtype == MC_DTYPE_BF16) {
-    if (wide) enqueue_merge<Bf16, 8>(o_parts, lse_parts, kv_splits, rows, out, lse, stream);
-    else enqueue_merge<Bf16, 1>(o_parts, lse_parts, kv_splits, rows, out, lse, stream);
-  } else {
+  if (dtype == MC_DTYPE_BF16 && head_dim == 128) {
+    if (wide) enqueue_merge<Bf16<128>, 8>(o_parts, lse_parts, kv_splits, rows, out, lse, stream);
+    else enqueue_merge<Bf16<128>, 1>(o_parts, lse_parts, kv_splits, rows, out, lse, stream);
+  } else if (dtype == MC_DTYPE_BF16 && head_dim == 64) {
+    if (wide) enqueue_merge<Bf16<64>, 8>(o_parts, lse_parts, kv_splits, rows, out, lse, stream);
+    else enqueue_merge<Bf16<64>, 1>(o_parts, lse_parts, kv_splits, rows, out, lse, stream);
+  } else if (dtype == MC_DTYPE_F32 && head_dim == 64) {
     if (wide) enqueue_merge<F32, 8>(o_parts, lse_parts, kv_splits, rows, out, lse, stream);
     else enqueue_merge<F32, 1>(o_parts, lse_parts, kv_splits, rows, out, lse, stream);
+  } else {
+    return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }

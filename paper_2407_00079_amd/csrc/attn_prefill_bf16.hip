@@ -38,10 +38,6 @@ namespace {
 typedef bf16x8 frag;
 typedef f32x4 acc4;
 
-constexpr int kD = 128;
-constexpr int kSteps = kD / 32;       // contraction steps of the scores over head_dim
-constexpr int kDTiles = kD / 16;      // 16-column tiles of the output
-constexpr int kRing = 8;              // K fragments of a block = V fragments of a block
 // The reference of a row's probabilities is kept kRefLift (log2 units) ABOVE the largest score it was last set
 // from, so probabilities are at most 2^-7 then and stay below 2 while later scores outgrow that maximum by less
 // than 8: "some probability reached 2" is bit 14 of a bf16 pattern, which an OR over the block's packed
@@ -50,47 +46,65 @@ constexpr int kRing = 8;              // K fragments of a block = V fragments of
 constexpr float kRefLift = 7.0f;
 constexpr float kRaiseAbove = 0.5f;
 constexpr uint32_t kGuardBits = 0x40004000u;
-static_assert(kRing == 2 * kSteps && kRing == kDTiles, "both phases walk the ring once");
 
 __device__ __forceinline__ acc4 mma(frag a, frag b, acc4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
-// LDS swizzles: 16-byte granule g of tile row r is stored at granule g ^ swz(r).
-// K: a fragment read has 16 lanes on 16 consecutive rows at the same logical granule -> spread
-//    them over all 16 positions of the 256-byte row.
-// V: a transpose read has 32 lanes on 8 consecutive rows x 32 bytes -> the 32-byte piece of a row
-//    moves by the row number, so the 8 rows cover all banks.
-__device__ __forceinline__ int k_swz(int row) { return row & 15; }
-__device__ __forceinline__ int v_swz(int row) { return (row & 7) << 1; }
+// Tile geometry for head_dim D (128: 256-byte rows, 64: 128-byte rows).
+template <int D>
+struct Geo {
+  static_assert(D == 128 || D == 64, "head_dim");
+  static constexpr int kRowB = D * 2;                    // bytes of a Q, K, V or O row
+  static constexpr int kGran = kRowB / 16;               // 16-byte granules of a row
+  static constexpr int kLineShift = D == 128 ? 0 : 1;    // log2 of the rows that share a 256-byte line of LDS banks
+  static constexpr int kSteps = D / 32;                  // contraction steps of the scores over head_dim
+  static constexpr int kDTiles = D / 16;                 // 16-column tiles of the output
+  static constexpr int kRing = kDTiles;                  // K fragments of a block = V fragments of a block
+  static_assert(kRing == 2 * kSteps, "both phases walk the ring once");
+  static constexpr int kPageHeadB = kPageTokens * kRowB; // one (page, KV head), contiguous in the pool
+  static constexpr int kKTileB = kTileKeys * kRowB;      // a K (or V) tile in LDS; rows dense, granules swizzled
+  static constexpr int kVBaseB = kBuffers * kKTileB;     // the K tiles of the three buffers, then the V tiles
+  static constexpr int kChunkRows = 1024 / kRowB;        // rows one wave copy instruction (1 KiB) covers
+  static constexpr int kPageChunks = kPageTokens / kChunkRows;
 
-// K fragment (key tile kt, head_dim step c) of a block: lane (j = l % 16, g = l / 16) reads
-// K[16 kt + j][32 c + 8 g .. + 7], i.e. granule 4 c + g of row 16 kt + j, stored at
-// (4 c + g) ^ j = ((c ^ (j >> 2)) << 2) | (g ^ (j & 3)):  address = k_lane_off ^ (c << 6)  (+ row offset)
-__device__ __forceinline__ int k_lane_off(int lane) {
-  const int j = lane & 15, g = lane >> 4;
-  return j * kRowBytes + ((((j >> 2) << 2) | (g ^ (j & 3))) << 4);
-}
-// ring slot i of a block's scores = (step i / 2, key tile i % 2)
-__device__ __forceinline__ frag load_k(const uint32_t (&kx)[kSteps], int off, int i) {
-  return *reinterpret_cast<MC_LDS const frag*>(kx[i >> 1] + off + (i & 1) * 16 * kRowBytes);
-}
-// V^T fragment (head_dim tile dt) of a block: lane (j, g) needs V[key][16 dt + j] for the keys 4 g + {0..3}
-// and 16 + 4 g + {0..3}.  The transpose read returns, to lane i of a 16-lane group, element i % 4 of
-// lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4: source lane s addresses key 4 g + s / 4, columns
-// 16 dt + 4 (s % 4) .. + 3.  That is 8 bytes at byte 32 dt + 8 (s % 4) of row rr = 4 g + s / 4: granule
-// 2 dt + (s % 4) / 2, stored at 2 (dt ^ (rr & 7)) + (s % 4) / 2:  address = v_lane_off ^ (dt << 5)
-__device__ __forceinline__ int v_lane_off(int lane) {
-  const int s = lane & 15, g = lane >> 4;
-  const int rr = 4 * g + (s >> 2);
-  return rr * kRowBytes + ((rr & 7) << 5) + (((s & 3) >> 1) << 4) + ((s & 1) << 3);
-}
-__device__ __forceinline__ frag load_v(const uint32_t (&vx)[kDTiles], int off, int dt) {
-  const uint32_t p = vx[dt] + off;
-  bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(uintptr_t)(p));
-  bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(uintptr_t)(p + 16 * kRowBytes));
-  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
+  // LDS swizzles: 16-byte granule g of tile row r is stored at granule g ^ swz(r).  The banks repeat every
+  // 256 bytes, i.e. every row (D 128) or every second row (D 64).
+  // K: a fragment read has 16 lanes on 16 consecutive rows at the same logical granule -> spread them over
+  //    all 16 granule positions of a 256-byte line (D 64: two rows per line, 8 positions each).
+  // V: a transpose read has 32 lanes on 8 consecutive rows x 32 bytes -> the 32-byte piece of a row moves
+  //    with the line number, so the 8 rows cover all banks.
+  static __device__ __forceinline__ int k_swz(int row) { return (row >> kLineShift) & (kGran - 1); }
+  static __device__ __forceinline__ int v_swz(int row) { return ((row >> kLineShift) & (kGran / 2 - 1)) << 1; }
+
+  // K fragment (key tile kt, head_dim step c) of a block: lane (j = l % 16, g = l / 16) reads
+  // K[16 kt + j][32 c + 8 g .. + 7], i.e. granule 4 c + g of row 16 kt + j, stored at (4 c) ^ g ^ swz(j)
+  // (the swizzle of row 16 kt + j is that of row j):  address = k_lane_off ^ (c << 6)  (+ row offset)
+  static __device__ __forceinline__ int k_lane_off(int lane) {
+    const int j = lane & 15, g = lane >> 4;
+    return j * kRowB + ((g ^ k_swz(j)) << 4);
+  }
+  // ring slot i of a block's scores = (step i / 2, key tile i % 2)
+  static __device__ __forceinline__ frag load_k(const uint32_t (&kx)[kSteps], int off, int i) {
+    return *reinterpret_cast<MC_LDS const frag*>(kx[i >> 1] + off + (i & 1) * 16 * kRowB);
+  }
+  // V^T fragment (head_dim tile dt) of a block: lane (j, g) needs V[key][16 dt + j] for the keys 4 g + {0..3}
+  // and 16 + 4 g + {0..3}.  The transpose read returns, to lane i of a 16-lane group, element i % 4 of
+  // lanes i / 4, 4 + i / 4, 8 + i / 4, 12 + i / 4: source lane s addresses key 4 g + s / 4, columns
+  // 16 dt + 4 (s % 4) .. + 3.  That is 8 bytes at byte 32 dt + 8 (s % 4) of row rr = 4 g + s / 4: 32-byte piece
+  // dt, stored at piece dt ^ (v_swz(rr) / 2) (rows rr and rr + 16 swizzle alike):  address = v_lane_off ^ (dt << 5)
+  static __device__ __forceinline__ int v_lane_off(int lane) {
+    const int s = lane & 15, g = lane >> 4;
+    const int rr = 4 * g + (s >> 2);
+    return rr * kRowB + (v_swz(rr) << 4) + (((s & 3) >> 1) << 4) + ((s & 1) << 3);
+  }
+  static __device__ __forceinline__ frag load_v(const uint32_t (&vx)[kDTiles], int off, int dt) {
+    const uint32_t p = vx[dt] + off;
+    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(uintptr_t)(p));
+    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((MC_LDS bf16x4*)(uintptr_t)(p + 16 * kRowB));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+};
 
 // combine a value over the 4 lane groups that share a query row (lanes l, l ^ 16, l ^ 32, l ^ 48)
 __device__ __forceinline__ float max_over_groups(float x) {
@@ -131,9 +145,15 @@ __device__ __forceinline__ void round_pair(PBlock& b, const Scores& p, int e) {
   const bf16x2 pr = __builtin_convertvector(pp, bf16x2);      // one v_cvt_pk_bf16_f32 (round to nearest even)
   b.w[e >> 3][(e & 7) >> 1] = __builtin_bit_cast(uint32_t, pr);
 }
-template <int WAVES, bool SPLIT>
+template <int D, int WAVES, bool SPLIT>
 __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) char smem[kBuffers * (kKTileBytes + kVTileBytes)];
+  typedef Geo<D> X;
+  // (these names hide the 256-byte-row constants of attn_device.h inside this kernel)
+  constexpr int kD = D, kSteps = X::kSteps, kDTiles = X::kDTiles, kRing = X::kRing, kRowBytes = X::kRowB,
+                kPageHeadBytes = X::kPageHeadB, kKTileBytes = X::kKTileB, kVTileBytes = X::kKTileB, kVBase = X::kVBaseB;
+  // tile bases are multiples of 8 KiB from a 256-byte aligned start: the XOR constants of the swizzle (< 256)
+  // never reach a tile base
+  __shared__ __attribute__((aligned(256))) char smem[kBuffers * (kKTileBytes + kVTileBytes)];
   constexpr int kTileRows = WAVES * 32;
 
   const int tid = threadIdx.x;
@@ -200,10 +220,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
   }
 
   // ---- global -> LDS, no registers in between (as in attn_prefill.hip): one wave instruction writes
-  //      1 KiB of LDS, 4 tile rows x 16 granules inside one page; lane i fetches, for granule position
-  //      i % 16 of row i / 16, the logical granule (i % 16) ^ swz(row).  The first wave of each SIMD copies.
+  //      1 KiB of LDS, 4 (D 64: 8) tile rows of 16 (8) granules inside one page; lane i fetches, for granule
+  //      position i % kGran of row i / kGran, the logical granule (i % kGran) ^ swz(row).  The first wave of
+  //      each SIMD copies.
   constexpr int kFetchWaves = WAVES / 2;
-  constexpr int kChunks = kTileKeys / 4;                      // 1 KiB chunks per K (or V) tile
+  constexpr int kChunks = kKTileBytes / 1024;                 // 1 KiB chunks per K (or V) tile
   constexpr int kFetch = kChunks / kFetchWaves;               // chunks per fetching wave
   static_assert(kChunks % kFetchWaves == 0 && kFetch <= 8, "tile must split evenly over the fetching waves");
   const char* kbase = reinterpret_cast<const char*>(a.k_pool) + (int64_t)item.kv_head * kPageHeadBytes;
@@ -221,7 +242,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
     if (!fetcher) return;
 #pragma unroll
     for (int i = 0; i < kFetch; ++i) {
-      int lp = tile * (kTileKeys / kPageTokens) + (wave_u + i * kFetchWaves) / 4;
+      int lp = tile * (kTileKeys / kPageTokens) + (wave_u + i * kFetchWaves) / X::kPageChunks;
       lp = lp < last_page ? lp : last_page;                  // never index the table past the request's pages
       pid_next[i] = btc[lp];
     }
@@ -230,10 +251,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
 #pragma unroll
     for (int i = 0; i < kFetch; ++i) pid[i] = pid_next[i];
   };
-  const int lane_row = (wave_u & 3) * 4 + (lane >> 4);       // row of the page this lane copies a granule of
-  const uint32_t k_src = (uint32_t)(lane_row * kRowBytes + (((lane & 15) ^ k_swz(lane_row)) << 4));
-  const uint32_t v_src = (uint32_t)(lane_row * kRowBytes + (((lane & 15) ^ v_swz(lane_row)) << 4));
-  static_assert(kFetchWaves % 4 == 0, "a fetching wave's chunks must all sit at the same rows of their pages");
+  // row of the page this lane copies a granule of (the swizzles depend on the row modulo 16 only)
+  const int lane_row = (wave_u % X::kPageChunks) * X::kChunkRows + lane / X::kGran;
+  const uint32_t k_src = (uint32_t)(lane_row * kRowBytes + (((lane % X::kGran) ^ X::k_swz(lane_row)) << 4));
+  const uint32_t v_src = (uint32_t)(lane_row * kRowBytes + (((lane % X::kGran) ^ X::v_swz(lane_row)) << 4));
+  static_assert(kFetchWaves % X::kPageChunks == 0, "a fetching wave's chunks must all sit at the same rows of their pages");
   auto fetch = [&](int tile, int buf) __attribute__((always_inline)) {
     if (!fetcher) return;
     const uint32_t dst0 = smem_base + buf * kKTileBytes + wave_u * 1024;
@@ -250,11 +272,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
       // first page instead; the causal mask hides the key
 #pragma unroll
       for (int i = 0; i < kFetch; ++i) {
-        const int row = (wave_u + i * kFetchWaves) * 4 + (lane >> 4);
+        const int row = (wave_u + i * kFetchWaves) * X::kChunkRows + lane / X::kGran;
         const bool in_seq = tile * kTileKeys + row < L;
         const int64_t page_off = (int64_t)pid[i] * page_stride;
-        const char* ks = kbase + (in_seq ? page_off + k_src : first_page_off + (k_src & 255));
-        const char* vs = vbase + (in_seq ? page_off + v_src : first_page_off + (v_src & 255));
+        const char* ks = kbase + (in_seq ? page_off + k_src : first_page_off + (k_src & (kRowBytes - 1)));
+        const char* vs = vbase + (in_seq ? page_off + v_src : first_page_off + (v_src & (kRowBytes - 1)));
         const uint32_t dst = dst0 + i * kFetchWaves * 1024;
         dma16(ks, dst);
         dma16(vs, dst + kVBase);
@@ -279,8 +301,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) o[dt][rt] = acc4{0.f, 0.f, 0.f, 0.f};
   const float c = a.scale_log2e;
-  const uint32_t k_lane = smem_base + k_lane_off(lane);
-  const uint32_t v_lane = smem_base + kVBase + v_lane_off(lane);
+  const uint32_t k_lane = smem_base + X::k_lane_off(lane);
+  const uint32_t v_lane = smem_base + kVBase + X::v_lane_off(lane);
   uint32_t kx[kSteps], vx[kDTiles];
 #pragma unroll
   for (int i = 0; i < kSteps; ++i) kx[i] = k_lane ^ (uint32_t)(i << 6);
@@ -293,7 +315,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
     s.zero();
 #pragma unroll
     for (int i = 0; i < kRing; ++i) {
-      const frag kf = load_k(kx, off, i);
+      const frag kf = X::load_k(kx, off, i);
       s.t[0][i & 1] = mma(kf, qf[i >> 1][0], s.t[0][i & 1]);
       s.t[1][i & 1] = mma(kf, qf[i >> 1][1], s.t[1][i & 1]);
       __builtin_amdgcn_sched_barrier(0);
@@ -351,7 +373,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
     const int off = buf * kVTileBytes + kb * 32 * kRowBytes;
 #pragma unroll
     for (int dt = 0; dt < kDTiles; ++dt) {
-      const frag vf = load_v(vx, off, dt);
+      const frag vf = X::load_v(vx, off, dt);
       o[dt][0] = mma(vf, pb.f(0), o[dt][0]);
       o[dt][1] = mma(vf, pb.f(1), o[dt][1]);
     }
@@ -370,7 +392,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
   auto load_k_ring = [&](int buf, int kb) __attribute__((always_inline)) {
     const int off = buf * kKTileBytes + kb * 32 * kRowBytes;
 #pragma unroll
-    for (int i = 0; i < kRing; ++i) ring[i] = load_k(kx, off, i);
+    for (int i = 0; i < kRing; ++i) ring[i] = X::load_k(kx, off, i);
   };
   // a probability of 2 or more (or not finite) means its score outgrew the reference: the block is then
   // recomputed against its true maxima (nothing was accumulated yet)
@@ -380,21 +402,20 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
     s_cur = s_next;
     s_next.zero();
     float m_ref[2];
-    uint32_t seen = 0;          // OR of the block's packed probabilities
+    constexpr int kPer = 16 / kRing;     // scores a step turns into probabilities
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) m_ref[rt] = SPLIT ? fmaxf(m_run[rt], kNoKeyYet) : m_run[rt];
 #pragma unroll
     for (int i = 0; i < kRing; ++i) {
       // the step's vector work first (two exponentials; rounding and summing trail one step behind the
       // exponentials they depend on), then its two MFMAs and the fragment read: measured best of the orders tried
-      const int e0 = 2 * i;
+      const int e0 = kPer * i;
 #pragma unroll
-      for (int e = e0; e < e0 + 2; ++e) s_cur.set(e, __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur.get(e), c, -m_ref[e >> 3])));
-      if (i > 0) round_pair(pb, s_cur, e0 - 2);
-      // the guard's OR trails the rounding by another step
-      if (i == 3) seen = pb.w[0][0] | pb.w[0][1];
-      if (i == 5) seen |= pb.w[0][2] | pb.w[0][3];
-      if (i == 7) seen |= pb.w[1][0] | pb.w[1][1];
+      for (int e = e0; e < e0 + kPer; ++e) s_cur.set(e, __builtin_amdgcn_exp2f(__builtin_fmaf(s_cur.get(e), c, -m_ref[e >> 3])));
+      if (i > 0) {
+#pragma unroll
+        for (int e = e0 - kPer; e < e0; e += 2) round_pair(pb, s_cur, e);
+      }
       __builtin_amdgcn_sched_barrier(0);
       // consecutive MFMAs always share an operand register (the K fragment inside a step, the Q fragment across
       // the steps of a head_dim chunk): odd steps take the row tiles in reverse order (+1 % under the power limit)
@@ -404,11 +425,13 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
         __builtin_amdgcn_sched_barrier(0);
         s_next.t[rb][i & 1] = mma(ring[i], qf[i >> 1][rb], s_next.t[rb][i & 1]);
       }
-      ring[i] = load_v(vx, off_v, i);
+      ring[i] = X::load_v(vx, off_v, i);
       __builtin_amdgcn_sched_barrier(0);
     }
-    round_pair(pb, s_cur, 14);
-    seen |= pb.w[1][2] | pb.w[1][3];
+#pragma unroll
+    for (int e = 16 - kPer; e < 16; e += 2) round_pair(pb, s_cur, e);
+    // OR of the block's packed probabilities
+    const uint32_t seen = pb.w[0][0] | pb.w[0][1] | pb.w[0][2] | pb.w[0][3] | pb.w[1][0] | pb.w[1][1] | pb.w[1][2] | pb.w[1][3];
     if (__builtin_amdgcn_ballot_w64((seen & kGuardBits) != 0) != 0) {
       qk_block(buf_cur, kb_cur, s_cur);
       settle_reference(s_cur, 0, std::false_type{});
@@ -429,7 +452,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
         }
         o[i][rb] = mma(ring[i], pb.f(rb), o[i][rb]);
       }
-      ring[i] = load_k(kx, off_k, i);
+      ring[i] = X::load_k(kx, off_k, i);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -541,8 +564,16 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
 
 hipError_t launch_attn_bf16(const AttnArgs& args, hipStream_t stream) {
   (void)hipGetLastError();   // drop any stale error of earlier, unrelated runtime calls
-  if (args.kv_splits > 0) attn_prefill_bf16_kernel<kWaves, true><<<args.n_items, kWaves * 64, 0, stream>>>(args);
-  else attn_prefill_bf16_kernel<kWaves, false><<<args.n_items, kWaves * 64, 0, stream>>>(args);
+  const bool split = args.kv_splits > 0;
+  if (args.head_dim == 128) {
+    if (split) attn_prefill_bf16_kernel<128, kWaves, true><<<args.n_items, kWaves * 64, 0, stream>>>(args);
+    else attn_prefill_bf16_kernel<128, kWaves, false><<<args.n_items, kWaves * 64, 0, stream>>>(args);
+  } else if (args.head_dim == 64) {
+    if (split) attn_prefill_bf16_kernel<64, kWaves, true><<<args.n_items, kWaves * 64, 0, stream>>>(args);
+    else attn_prefill_bf16_kernel<64, kWaves, false><<<args.n_items, kWaves * 64, 0, stream>>>(args);
+  } else {
+    return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

@@ -15,7 +15,7 @@ mc_status check_params(const mc_attn_params* p) {
   if (p->num_q_heads % p->num_kv_heads != 0) return MC_ERR_SHAPE;
   if (p->dtype != MC_DTYPE_BF16 && p->dtype != MC_DTYPE_F32) return MC_ERR_UNSUPPORTED;
   if (p->page_size != 16) return MC_ERR_UNSUPPORTED;
-  if (p->dtype == MC_DTYPE_BF16 && p->head_dim != 128) return MC_ERR_UNSUPPORTED;
+  if (p->dtype == MC_DTYPE_BF16 && p->head_dim != 128 && p->head_dim != 64) return MC_ERR_UNSUPPORTED;
   if (p->dtype == MC_DTYPE_F32 && p->head_dim != 64) return MC_ERR_UNSUPPORTED;
   if (!(p->softmax_scale >= 0.f) || std::isinf(p->softmax_scale)) return MC_ERR_SHAPE;
   return MC_OK;

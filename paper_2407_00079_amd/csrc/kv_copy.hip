@@ -133,16 +133,17 @@ __global__ __launch_bounds__(256) void kv_check_page_ids_kernel(const int32_t* _
 
 // Append (paper Section 3 step 2: the chunk's new KVCache is kept in the request's pages):
 // one thread moves one 16-byte granule of one (token, KV head) row of K and of V.  The request
-// of a token is found by bisection of the per-request table; rows are 256 bytes for both dtypes.
+// of a token is found by bisection of the per-request table; a row has 1 << gran_shift granules
+// (256 bytes for bf16 head_dim 128 and fp32 head_dim 64, 128 bytes for bf16 head_dim 64).
 __global__ __launch_bounds__(256) void kv_append_kernel(const u32x4* __restrict__ k_new, const u32x4* __restrict__ v_new,
                                                         u32x4* __restrict__ k_pool, u32x4* __restrict__ v_pool,
                                                         const int32_t* __restrict__ block_tables, int32_t max_pages,
                                                         const AttnReq* __restrict__ reqs, int32_t batch,
-                                                        int64_t total_vecs, int32_t Hkv) {
+                                                        int64_t total_vecs, int32_t Hkv, int32_t gran_shift) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= total_vecs) return;
-  const int gran = (int)(idx & 15);
-  const int64_t row = idx >> 4;                 // (token, head)
+  const int gran = (int)(idx & ((1 << gran_shift) - 1));
+  const int64_t row = idx >> gran_shift;        // (token, head)
   const int g = (int)(row % Hkv);
   const int32_t tok = (int32_t)(row / Hkv);
   int lo = 0, hi = batch - 1;                   // last request with q_off <= tok and at least one token
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const u32x4* __restrict_
   const AttnReq rq = reqs[lo];
   const int32_t pos = rq.prefix + (tok - rq.q_off);
   const int64_t page = block_tables[(int64_t)lo * max_pages + (pos >> 4)];
-  const int64_t dst = (((page * Hkv + g) << 4) + (pos & 15)) * 16 + gran;
+  const int64_t dst = ((((page * Hkv + g) << 4) + (pos & 15)) << gran_shift) + gran;
   k_pool[dst] = k_new[idx];
   v_pool[dst] = v_new[idx];
 }
@@ -179,12 +180,13 @@ hipError_t launch_kv_check_page_ids(const int32_t* page_ids, int64_t n, int64_t 
 
 hipError_t launch_kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
                             const int32_t* block_tables, int32_t max_pages, const AttnReq* reqs, int32_t batch,
-                            int64_t total_new, int32_t Hkv, hipStream_t stream) {
-  const int64_t total_vecs = total_new * Hkv * 16;
+                            int64_t total_new, int32_t Hkv, int32_t row_bytes, hipStream_t stream) {
+  const int32_t gran_shift = row_bytes == 256 ? 4 : 3;      // 256- or 128-byte rows
+  const int64_t total_vecs = (total_new * Hkv) << gran_shift;
   (void)hipGetLastError();
   kv_append_kernel<<<(unsigned)((total_vecs + 255) / 256), 256, 0, stream>>>(
       (const u32x4*)k_new, (const u32x4*)v_new, (u32x4*)k_pool, (u32x4*)v_pool, block_tables, max_pages, reqs, batch,
-      total_vecs, Hkv);
+      total_vecs, Hkv, gran_shift);
   return hipGetLastError();
 }
 

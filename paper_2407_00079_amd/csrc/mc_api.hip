@@ -13,6 +13,9 @@ namespace {
 
 using namespace mc::host;
 
+// bytes of one K or V row of one KV head
+int32_t row_bytes_of(const mc_attn_params* p) { return p->head_dim * (p->dtype == MC_DTYPE_BF16 ? 2 : 4); }
+
 // Pinned host slots the work list is written to before its asynchronous upload.  A slot is
 // reused only after the event recorded behind its last upload has completed, so the host copy
 // outlives the transfer.  A call never waits for the stream's earlier work: if every slot is
@@ -180,6 +183,7 @@ mc_status launch_planned_attn(const mc_attn_params* p, const mc_attn_plan* plan,
   args.Hkv = p->num_kv_heads;
   args.G = p->num_q_heads / p->num_kv_heads;
   args.max_pages = max_pages_per_req;
+  args.head_dim = p->head_dim;
   args.scale_log2e = attn_scale_log2e(p);
   args.n_items = plan->n_items;
   args.kv_splits = plan->kv_splits;
@@ -365,7 +369,7 @@ mc_status mc_kv_append_run(const mc_attn_params* p, const mc_attn_plan* plan, co
   const char* ws = reinterpret_cast<const char*>(workspace);
   if (mc::launch_kv_append(k_new, v_new, k_pool, v_pool, block_tables, max_pages_per_req,
                            reinterpret_cast<const mc::AttnReq*>(ws + plan->reqs_offset), plan->batch, total_new,
-                           p->num_kv_heads, reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
+                           p->num_kv_heads, row_bytes_of(p), reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return MC_ERR_HIP;
   return MC_OK;
 }
@@ -384,7 +388,7 @@ int32_t mc_prefill_attn_suggest_kv_splits(const mc_attn_params* p, const int32_t
 mc_status mc_attn_merge_lse(const float* o_parts, const float* lse_parts, int32_t kv_splits, int64_t rows,
                             int32_t head_dim, int32_t dtype, void* out, float* lse, void* hip_stream) {
   if (kv_splits < 1 || kv_splits > MC_MAX_KV_SPLITS || rows < 0 || head_dim <= 0) return MC_ERR_SHAPE;
-  if (!((dtype == MC_DTYPE_BF16 && head_dim == 128) || (dtype == MC_DTYPE_F32 && head_dim == 64)))
+  if (!((dtype == MC_DTYPE_BF16 && (head_dim == 128 || head_dim == 64)) || (dtype == MC_DTYPE_F32 && head_dim == 64)))
     return MC_ERR_UNSUPPORTED;
   if (rows == 0) return MC_OK;
   if (o_parts == nullptr || lse_parts == nullptr || out == nullptr) return MC_ERR_NULL;
@@ -392,7 +396,7 @@ mc_status mc_attn_merge_lse(const float* o_parts, const float* lse_parts, int32_
       !aligned4(lse))
     return MC_ERR_ALIGN;
   if (rows > INT32_MAX) return MC_ERR_RANGE;
-  if (mc::launch_attn_merge(dtype, o_parts, lse_parts, kv_splits, rows, out, lse,
+  if (mc::launch_attn_merge(dtype, head_dim, o_parts, lse_parts, kv_splits, rows, out, lse,
                             reinterpret_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return MC_ERR_HIP;
   return MC_OK;
@@ -448,7 +452,7 @@ mc_status mc_kv_append_paged(const mc_attn_params* p, const void* k_new, const v
   if (!g_staging.release_after(slot, stream)) return MC_ERR_HIP;
   if (mc::launch_kv_append(k_new, v_new, k_pool, v_pool, block_tables, max_pages_per_req,
                            reinterpret_cast<const mc::AttnReq*>(workspace), batch, total_new, p->num_kv_heads,
-                           stream) != hipSuccess)
+                           row_bytes_of(p), stream) != hipSuccess)
     return MC_ERR_HIP;
   return MC_OK;
 }

@@ -18,6 +18,7 @@ struct AttnArgs {
   const AttnItem* items;
   const AttnReq* reqs;
   int32_t Hq, Hkv, G, max_pages;
+  int32_t head_dim;   // bf16: 128 or 64; fp32: 64
   float scale_log2e;  // softmax scale * log2(e): scores go through exp2
   int32_t n_items;
   // split launches (kv_splits > 0): partial results go to o_parts [kv_splits, rows_total, D] fp32 and
@@ -35,7 +36,7 @@ hipError_t launch_attn(int dtype, const AttnArgs& args, hipStream_t stream);
 hipError_t launch_attn_bf16(const AttnArgs& args, hipStream_t stream);
 
 // enqueue the merge of kv_splits partial results over `rows` rows into out (dtype) and lse (or null)
-hipError_t launch_attn_merge(int dtype, const float* o_parts, const float* lse_parts, int kv_splits, int64_t rows,
+hipError_t launch_attn_merge(int dtype, int head_dim, const float* o_parts, const float* lse_parts, int kv_splits, int64_t rows,
                              void* out, float* lse, hipStream_t stream);
 
 // enqueue gather (pack) or scatter (unpack) of n pages of page_bytes for K and V; `order` (or null)
@@ -51,10 +52,10 @@ hipError_t launch_kv_page_order(const int32_t* page_ids, int64_t n, int32_t* ord
 hipError_t launch_kv_check_page_ids(const int32_t* page_ids, int64_t n, int64_t num_pages, int32_t* report,
                                     hipStream_t stream);
 
-// enqueue the scatter of total_new tokens' K/V rows (256 bytes per KV head) into their page slots
+// enqueue the scatter of total_new tokens' K/V rows (row_bytes = 256 or 128 per KV head) into their page slots
 hipError_t launch_kv_append(const void* k_new, const void* v_new, void* k_pool, void* v_pool,
                             const int32_t* block_tables, int32_t max_pages, const AttnReq* reqs, int32_t batch,
-                            int64_t total_new, int32_t Hkv, hipStream_t stream);
+                            int64_t total_new, int32_t Hkv, int32_t row_bytes, hipStream_t stream);
 
 // enqueue digest + chain kernels (offset tables on the device; max_blocks = most blocks of any request)
 hipError_t launch_prefix_hash(const int32_t* tokens, const int64_t* tok_off, const int64_t* key_off, int batch,

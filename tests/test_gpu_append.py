@@ -31,6 +31,7 @@ def _host(t, like):
     (W.BF16, 8, 8, 128, [0, 0, 0], [0, 0, 700], 80),                  # empty requests ahead of the only chunk
     (W.BF16, 64, 8, 128, [1000, 15, 4097], [513, 1, 255], 512),       # LLaMA2-70B heads, several blocks and a ragged tail
     (W.BF16, 2, 1, 128, [5] * 40, [1] * 40, 64),                      # many one-token requests (decode-shaped)
+    (W.BF16, 8, 4, 64, [37, 0, 16, 5], [50, 33, 1, 0], 64),           # 128-byte rows (bf16, head_dim 64)
 ])
 def test_append_matches_oracle(oracle, dtype, Hq, Hkv, D, prefix, new, pages):
     print(f"append case {dtype} Hq={Hq} Hkv={Hkv} prefix={prefix[:4]} new={new[:4]}", flush=True)

@@ -50,6 +50,19 @@ def test_bf16_small_shapes(oracle, Hq, Hkv, P, C):
 
 
 @pytest.mark.parametrize("Hq,Hkv,P,C", [
+    (8, 1, [256], [128]),              # several Q tiles, prefix + diagonal tiles
+    (8, 2, [0], [200]),                # no prefix, ragged tail
+    (16, 2, [100], [37]),              # prefix not page aligned, partial last page
+    (4, 4, [64], [130]),               # MHA
+    (4, 2, [33, 0, 512, 16], [5, 17, 1, 70]),   # varlen batch incl. a single-row request
+    (8, 1, [2000], [300]),             # many pipelined tiles
+])
+def test_bf16_head_dim_64_small_shapes(oracle, Hq, Hkv, P, C):
+    case = W.make_attn_case(300 + Hq + sum(C), W.BF16, Hq, Hkv, 64, 16, P, C, 256)
+    run_full(oracle, case, what=f"bf16 D=64 {Hq}/{Hkv}")
+
+
+@pytest.mark.parametrize("Hq,Hkv,P,C", [
     (4, 1, [0], [70]),
     (6, 2, [45, 16], [33, 1]),
     (2, 2, [130], [66]),

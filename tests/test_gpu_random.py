@@ -29,7 +29,7 @@ def random_shape(seed):
         new[0] = 17
     while sum(c * (p + c) for p, c in zip(prefix, new)) * Hkv * G > 6e8:    # keep the oracle within seconds
         new = [max(c // 2, 1) if c else 0 for c in new]
-    dtype, D = (W.F32, 64) if seed % 6 == 5 else (W.BF16, 128)
+    dtype, D = (W.F32, 64) if seed % 6 == 5 else (W.BF16, 64) if seed % 6 == 2 else (W.BF16, 128)
     pages = sum(-(-(p + c) // 16) for p, c in zip(prefix, new)) + 8
     q_scale = float(rng.choice([1.0, 1.0, 3.0, 8.0])) if big else 1.0
     return dtype, Hkv * G, Hkv, D, prefix, new, pages, q_scale

@@ -42,6 +42,8 @@ def run_split(case, kv_splits, scale=0.0):
     (W.BF16, 8, 2, 128, [130], [70], 32, 1),                # one slice = the whole row, through the partial path
     (W.BF16, 8, 1, 128, [20000, 300], [8, 3], 1300, 256),   # the most slices the interface takes: one or two tiles each
     (W.F32, 4, 1, 64, [3000], [5], 200, 9),                 # fp32 through the eight split lanes of the merge
+    (W.BF16, 8, 2, 64, [700, 30], [40, 150], 128, 3),       # bf16 with 128-byte rows (head_dim 64)
+    (W.BF16, 8, 1, 64, [3000], [8], 200, 11),               # the same through the eight split lanes of the merge
 ])
 def test_split_partials_and_merge_match_oracle(oracle, dtype, Hq, Hkv, D, prefix, new, pages, kv_splits):
     print(f"split case {dtype} Hq={Hq} Hkv={Hkv} prefix={prefix} new={new} splits={kv_splits}", flush=True)

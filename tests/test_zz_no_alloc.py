@@ -56,6 +56,14 @@ def test_fp32_and_many_heads(oracle):
     check_close(d.out.cpu().numpy().astype(np.float64), ref, W.F32, "fp32 against the oracle")
 
 
+def test_bf16_head_dim_64(oracle):
+    case = W.make_attn_case(104, W.BF16, 16, 2, 64, 16, [300, 0, 41], [130, 70, 9], 128)
+    d, want_o, want_l = run_both(case)
+    same(d, want_o, want_l, W.BF16, "bf16, head_dim 64")
+    ref, lse_ref, _ = oracle.case_full(case)
+    check_close(d.out.float().cpu().numpy().astype(np.float64), ref, W.BF16, "bf16 head_dim 64 against the oracle")
+
+
 def test_limits_and_noops():
     p = B.attn_params(64, 8, 128, 16, 4096, "bf16")
     FAKE = 0x7F0000001000
