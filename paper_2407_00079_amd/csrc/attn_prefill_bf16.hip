@@ -432,7 +432,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
     for (int e = 16 - kPer; e < 16; e += 2) round_pair(pb, s_cur, e);
     // OR of the block's packed probabilities
     const uint32_t seen = pb.w[0][0] | pb.w[0][1] | pb.w[0][2] | pb.w[0][3] | pb.w[1][0] | pb.w[1][1] | pb.w[1][2] | pb.w[1][3];
-    if (__builtin_amdgcn_ballot_w64((seen & kGuardBits) != 0) != 0) {
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64((seen & kGuardBits) != 0) != 0, 0)) {   // (laid out behind the loop)
       qk_block(buf_cur, kb_cur, s_cur);
       settle_reference(s_cur, 0, std::false_type{});
       probabilities(s_cur, pb);
@@ -512,9 +512,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_prefill_bf16_kernel(const Att
     for (;;) {
       if (tile >= n_plain) break;
       // Where the loop body sits relative to the 64-byte instruction fetch lines changes its speed by up to
-      // 3.5 % (all 16 offsets measured on the 128k-context workload); pin the best one, so that edits
-      // elsewhere in the kernel cannot move it.
-      asm volatile(".p2align 6\n\ts_nop 0");
+      // 3.5 % (all 16 offsets measured on the 128k-context workload, with the rare recompute path laid out
+      // behind the loop); pin the best one, so that edits elsewhere in the kernel cannot move it.
+      asm volatile(".p2align 6");
       pipelined_tile(std::integral_constant<int, 0>{});
       if (tile >= n_plain) break;
       pipelined_tile(std::integral_constant<int, 1>{});
