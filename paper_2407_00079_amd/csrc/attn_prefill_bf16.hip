@@ -106,14 +106,10 @@ struct Geo {
   }
 };
 
-// combine a value over the 4 lane groups that share a query row (lanes l, l ^ 16, l ^ 32, l ^ 48)
+// largest of a value over the 4 lane groups that share a query row (lanes l, l ^ 16, l ^ 32, l ^ 48)
 __device__ __forceinline__ float max_over_groups(float x) {
   x = fmaxf(x, __shfl_xor(x, 16, 64));
   return max_with_other_half(x);
-}
-__device__ __forceinline__ float sum_over_groups(float x) {
-  x += __shfl_xor(x, 16, 64);
-  return sum_with_other_half(x);
 }
 
 // The scores of one 32-key block as a lane holds them: s[rt][kt] is the accumulator of score tile
