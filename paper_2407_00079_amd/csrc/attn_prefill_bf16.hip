@@ -15,10 +15,11 @@
 //     + {0..3} - the rows of its lane group in the two 16x16 score tiles S^T = K Q^T.  The
 //     probabilities of a lane are therefore already the B operand of O^T += V^T P^T (a 32-key
 //     contraction in that key order); V^T fragments are fetched in the same order with two LDS
-//     transpose reads.  Row maxima and sums are in-lane over 8 values plus an exchange between
-//     the 4 lane groups, which the steady state needs only at the very end.
-//   * Per 32-key block: 16 score MFMAs (2 key tiles x 2 row tiles x 4 head_dim steps of 32) and
-//     16 P V MFMAs (8 head_dim tiles x 2 row tiles), 8 K fragments and 8 V fragments from LDS.
+//     transpose reads.  Row maxima (diagonal tiles and the rare recompute path only) are in-lane
+//     over 8 values plus an exchange between the 4 lane groups.
+//   * Per 32-key block at head_dim 128: 16 score MFMAs (2 key tiles x 2 row tiles x 4 head_dim
+//     steps of 32) and 16 P V MFMAs (8 head_dim tiles x 2 row tiles), 8 K fragments and 8 V
+//     fragments from LDS; at head_dim 64 half of each (see Geo).
 //   * K/V tiles, their copy into LDS, the page walk, the lazy softmax reference, the two-phase
 //     ring schedule and the half-step skew of the two waves of a SIMD are those of
 //     attn_prefill.hip; the swizzles differ (fragment shapes differ).
