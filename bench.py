@@ -566,6 +566,28 @@ def main():
                     "frac_fp32_mfma_peak": round(fl / (us * 1e-6) / 1e12 / 157.3, 4)}
 
         result["attn_fp32"] = fp32_attention()
+
+        # the bf16 instantiation for head_dim 64 (128-byte rows) at configuration 2's lengths; no workload uses it
+        def bf16_head_dim_64():
+            P2, C2, Hq2, Hkv2 = 8192, 8192, 64, 8
+            npg = (P2 + C2) // 16
+            g2 = torch.Generator(device=dev)
+            g2.manual_seed(20240702)
+            q2 = torch.randn(C2, Hq2, 64, device=dev, dtype=torch.bfloat16, generator=g2)
+            k2 = torch.randn(npg, Hkv2, 16, 64, device=dev, dtype=torch.bfloat16, generator=g2)
+            v2 = torch.randn(npg, Hkv2, 16, 64, device=dev, dtype=torch.bfloat16, generator=g2)
+            bt2 = torch.randperm(npg, device=dev, generator=g2).to(torch.int32).reshape(1, npg).contiguous()
+            prm = B.attn_params(Hq2, Hkv2, 64, 16, npg, "bf16")
+            out2 = torch.empty_like(q2)
+            ws2 = torch.empty(B.mc_prefill_attn_workspace_bytes(prm, 1, C2), dtype=torch.uint8, device=dev)
+            s2 = torch.cuda.current_stream()
+            us = timed_loop(lambda: B.mc_prefill_attn_paged(prm, q2, k2, v2, bt2, [P2], [C2], out2, None, ws2, s2), 10, 3, s2)
+            fl = 4 * 64 * Hq2 * (C2 * P2 + C2 * (C2 + 1) // 2)
+            return {"workload": "bf16, 64/8 heads, head_dim 64, P=8192, C=8192", "flops": fl, "ms": round(us / 1e3, 3),
+                    "tflops": round(fl / (us * 1e-6) / 1e12, 1),
+                    "pct_mfma_peak": round(100 * fl / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2)}
+
+        result["attn_bf16_head_dim_64"] = bf16_head_dim_64()
         torch.cuda.empty_cache()
         # a small chunk against a long prefix (16 new tokens behind 131056 cached ones, 64/8 heads): 8 work
         # items for 256 CUs unless the keys are split
