@@ -139,6 +139,22 @@ def test_large_scores(oracle):
     run_full(oracle, case, what="q x30")
 
 
+def test_bf16_head_dim_64_at_full_size_on_sampled_rows(oracle):
+    """Configuration 2's lengths and heads with 128-byte rows: 2048 work items, every XCD list, many pipelined tiles."""
+    case = W.make_attn_case(77, W.BF16, 64, 8, 64, 16, [8192], [8192], 1200)
+    dc = DeviceCase(case)
+    dc.run()
+    out, lse = dc.result()
+    assert np.isfinite(out).all() and np.isfinite(lse).all()     # every row written
+    rows = W.sample_rows(case, 1100, seed=77)
+    got, got_lse = gather_rows(out, lse, case, rows)
+    ref, lse_ref, _ = oracle.case_rows(case, rows)
+    max_abs, rel_l2 = check_close(got, ref, W.BF16, "bf16 head_dim 64, full size")
+    lse_err = np.abs(got_lse - lse_ref).max()
+    print(f"bf16 head_dim 64 full size: max_abs {max_abs:.3e} rel_l2 {rel_l2:.3e} lse {lse_err:.3e}", flush=True)
+    assert lse_err <= TOL[W.BF16]["lse_abs"]
+
+
 def test_scores_that_keep_outgrowing_the_reference(oracle):
     """Scores that rise along the keys at eight different rates, one per head (from 0.3 to 20 log2 units per 32-key
     block): the lazy softmax reference is outgrown by just under and just over its margin again and again, in the
