@@ -290,6 +290,30 @@ def main():
                                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                                           "us_per_layer": round(us, 2), "bytes_per_launch": copy_bytes,
                                           "traffic": hbm(name.split("_")[0])}
+        # the same 80 layers with the launches alternating between two streams, so that the tail of one launch
+        # overlaps the start of the next (layers are independent of each other): what is left of the gap to the
+        # steady-state rate once the fixed cost per launch is hidden
+        s_a, s_b = torch.cuda.Stream(), torch.cuda.Stream()
+        for name, fn in (("pack", pack), ("unpack", unpack)):
+            for l in range(LAY):
+                fn(l, s_a if l % 2 == 0 else s_b)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            joined = torch.cuda.Event()
+            e0.record(s_a)
+            s_b.wait_event(e0)
+            for i in range(80):
+                fn(i % LAY, s_a if i % 2 == 0 else s_b)
+            joined.record(s_b)
+            s_a.wait_event(joined)
+            e1.record(s_a)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 80
+            gbs = copy_bytes / (us * 1e-6) / 1e9
+            result[f"roofline_{name}_two_streams"] = {
+                "kernel": f"kv_copy_kernel<{name}>", "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "us_per_layer": round(us, 2),
+                "what": "80 layers, launches alternating between two streams (consecutive launches overlap)"}
         # what a copy of the same bytes reaches on this board with nothing scattered: the same kernel with the pages
         # in pool order (ids 0 .. n-1), the runtime's device-to-device copy, and the stand-alone probes: the read-only
         # and write-only halves of the access pattern, fixed cost per launch and steady-state rate
